@@ -1,0 +1,160 @@
+#!/usr/bin/env python3
+"""Bench of the MM-DiT joint-attention hot path on one MI355X.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload flux_1024]
+
+A step is one attention call of one DiT layer at the FLUX-like 1024^2 shape
+(B=1, H=24, N=4608, D=128, bf16): the dense entry point (Sparse-Attention action 0),
+the shape the headline metric is quoted on.  Inputs are synthetic (i.i.d. N(0,1)
+rounded to bf16), resident in HBM before the timed region.  The same run then times
+the block-sparse entry point (mask compaction + attention) at each density of the
+workload and reports time / (effective density x dense time), and times the fp64
+CPU oracle on a bounded sample of rows of the same workload.
+
+Prints ONE JSON line:
+  value      effective TFLOP/s = 4 B H kv_len^2 D density / time  (density 1 for dense)
+  roofline   dominant kernel (the attention kernel) against the bf16 MFMA peak, from
+             HIP-event durations of each launch on the launch stream
+  cpu_baseline  the oracle, as it stands, on this machine's host cores
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA peak (published, no sparsity)
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="flux_1024")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-sparse", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=15.0)
+    return ap.parse_args()
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU; --gpus above 1 is not supported "
+              "(no collectives or sharding are part of it).", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    import paper_2509_22323_amd as ra
+    import workloads as wl
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 3
+    torch.cuda.set_device(0)
+    ra.library()                                   # fail loudly if the HIP library is missing
+
+    w = wl.WORKLOADS[args.workload]
+    q, k, v = w.qkv()
+
+    def dev(bits):
+        return torch.from_numpy(bits.view(np.int16)).cuda().view(torch.bfloat16)
+
+    dq, dk, dv = dev(q), dev(k), dev(v)
+    do = torch.empty_like(dq)
+    ws = torch.empty(ra.rapid_attn_workspace_bytes(w.B, w.H, w.N, w.D, w.block), dtype=torch.uint8,
+                     device="cuda")
+    dense_flops = w.dense_flops()
+
+    def time_calls(fn, steps, warmup):
+        """(wall ms per step, mean and min HIP-event ms per call) over `steps` calls."""
+        for _ in range(warmup):
+            fn()
+        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+              for _ in range(steps)]
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for a, b in ev:
+            a.record()
+            fn()
+            b.record()
+        torch.cuda.synchronize()
+        wall = (time.perf_counter() - t0) * 1e3 / steps
+        durs = [a.elapsed_time(b) for a, b in ev]
+        return wall, float(np.mean(durs)), float(np.min(durs))
+
+    # ---- the timed K steps: dense entry point
+    wall_ms, ev_mean, ev_min = time_calls(
+        lambda: ra.rapid_attn_dense(dq, dk, dv, do, w.kv_len), args.steps, args.warmup)
+    value = dense_flops / (wall_ms * 1e-3) / 1e12
+    achieved = dense_flops / (ev_mean * 1e-3) / 1e12
+
+    out = {
+        "metric": "effective TFLOP/s (4*B*H*N^2*D*density), dense joint attention",
+        "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(wall_ms, 5), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{w.name}: B={w.B} H={w.H} N={w.N} kv_len={w.kv_len} D={w.D} "
+                               f"dense (action 0), one layer's attention per step",
+                   "flops_per_step": dense_flops, "entry": "rapid_attn_dense"},
+        "pct_of_bf16_mfma_peak": round(100.0 * value / PEAK_BF16_TFLOPS, 2),
+        "roofline": {"bound": "mfma", "kernel": f"attn_kernel<D={w.D}>", "achieved": round(achieved, 2),
+                     "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                     "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": None,
+                     "launch_ms_mean": round(ev_mean, 5), "launch_ms_min": round(ev_min, 5)},
+    }
+
+    # ---- block-sparse entry point at the workload's densities (compaction included)
+    if not args.no_sparse:
+        sparse = []
+        for d in w.densities:
+            mask = w.mask(d)
+            eff = wl.effective_density(mask, w.block, w.kv_len)
+            dm = torch.from_numpy(mask).cuda()
+            s_wall, s_mean, s_min = time_calls(
+                lambda: ra.rapid_attn_block_sparse(dq, dk, dv, do, dm, w.block, w.kv_len, 0.0, ws),
+                max(20, args.steps // 2), max(5, args.warmup // 2))
+            sparse.append({"density_nominal": d, "density_effective": round(eff, 4),
+                           "ms": round(s_mean, 5),
+                           "eff_tflops": round(dense_flops * eff / (s_mean * 1e-3) / 1e12, 2),
+                           "time_over_density_x_dense": round(s_mean / (eff * ev_mean), 3)})
+        out["sparse"] = sparse
+
+    # ---- the oracle on this machine's host cores, bounded sample of rows of the same workload
+    if not args.no_cpu_baseline:
+        import oracle
+        rng = np.random.default_rng(1)
+
+        def rows(n):
+            return np.stack([rng.integers(w.B, size=n), rng.integers(w.H, size=n),
+                             rng.integers(w.kv_len, size=n)], axis=1).astype(np.int32)
+
+        flops_per_row = 4.0 * w.kv_len * w.D
+        t0 = time.perf_counter()
+        oracle.attention_rows(q, k, v, rows(256), w.kv_len)
+        pilot = time.perf_counter() - t0
+        n = int(max(256, min(w.B * w.H * w.kv_len, args.cpu_seconds / max(pilot, 1e-6) * 256)))
+        t0 = time.perf_counter()
+        oracle.attention_rows(q, k, v, rows(n), w.kv_len)
+        dt = time.perf_counter() - t0
+        out["cpu_baseline"] = {"value": round(n * flops_per_row / dt / 1e12, 6), "unit": "TFLOP/s",
+                               "cores": oracle.threads(), "kind": "oracle",
+                               "sample": f"{n} random output rows of {w.name} dense "
+                                         f"({n * flops_per_row / 1e9:.1f} GFLOP fp64) in {dt:.1f} s; "
+                                         f"full call would take {dense_flops / (n * flops_per_row) * dt:.0f} s"}
+
+    print(json.dumps(out), flush=True)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

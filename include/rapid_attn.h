@@ -1,0 +1,114 @@
+/*
+ * rapid_attn.h -- C ABI of the MI355X (gfx950) MM-DiT joint-attention library.
+ *
+ * One call = the self-attention of ONE DiT layer over the joint image+text
+ * token sequence, for all samples and heads (RAPID^3 Sec. 3.1, Eq. 1: F_SA),
+ * either dense or with the attention map pruned to a per-(sample, head) set
+ * of (query-block, key-block) tiles (Sec. 3.2 "Level-3: Sparse-Attention",
+ * Eq. 4: F_SA_sparse, controlled per layer and per head).
+ *
+ * Mapping from the Sparse-Attention action of Sec. 3.3 (c):
+ *   a = 0            -> rapid_attn_dense
+ *   a in 1..N_sparse -> rapid_attn_block_sparse with that action's mask
+ *   cache reused     -> no call (the policy is inactive on such a step)
+ * A CFG pair (App. B: SD3 runs cond + null as a batch of two under one
+ * action) passes the same mask for both samples.
+ *
+ * Semantics, for sample b, head h, query row r (M = 1 everywhere when dense):
+ *   r >= kv_len                                   -> O[b,h,r,:] = 0
+ *   A = { c < kv_len : M[b,h,r/block,c/block] != 0 }
+ *   A empty                                       -> O[b,h,r,:] = 0
+ *   else   O[b,h,r,:] = sum_{c in A} softmax_A(scale * Q[r].K[c]) V[c,:]
+ * Pruned keys are removed before the softmax; K/V tiles of pruned blocks and
+ * rows at or beyond kv_len are never multiplied in (NaN/Inf there are inert).
+ * Arithmetic: bf16 inputs, bf16 MFMA with fp32 accumulation, fp32 online
+ * softmax, probabilities rounded to bf16 before the PV product, bf16 output.
+ *
+ * Memory: every pointer except `stream` is a DEVICE pointer owned by the
+ * caller.  Q, K, V, O are bf16 [B, H, N, D] contiguous, D fastest.  Q/K/V/mask
+ * are read-only; O is fully overwritten ([B,H,N,D], padded rows included) and
+ * must not alias an input.  The library allocates nothing, keeps no state
+ * between calls and never synchronises: kernels are enqueued on `stream`
+ * (a hipStream_t; NULL = the default stream) and the call returns at once.
+ *
+ * Errors: every argument check happens on the host before any launch, so each
+ * code below is reachable without a GPU.  On error nothing is launched.
+ */
+#ifndef RAPID_ATTN_H
+#define RAPID_ATTN_H
+
+#include <stddef.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define RAPID_ATTN_VERSION 100
+
+/* exported with default visibility; everything else in the library is hidden */
+#define RAPID_API __attribute__((visibility("default")))
+
+typedef enum {
+    RAPID_OK              =  0,
+    RAPID_ERR_NULL        = -1,  /* a required pointer is NULL                        */
+    RAPID_ERR_SHAPE       = -2,  /* B,H,N <= 0; kv_len outside 1..N; N % block != 0   */
+    RAPID_ERR_UNSUPPORTED = -3,  /* D not in {64,128}; block not in {64,128}          */
+    RAPID_ERR_ALIGN       = -4,  /* q/k/v/o/workspace not 16-byte aligned             */
+    RAPID_ERR_WORKSPACE   = -5,  /* workspace NULL or smaller than required           */
+    RAPID_ERR_DEVICE      = -6   /* the HIP runtime refused a launch                  */
+} rapid_status;
+
+/*
+ * Dense joint attention (Sec. 3.1 Eq. 1; action 0 of Sec. 3.3 (c)).
+ *   q,k,v   device, bf16 [B,H,N,D]           o   device, bf16 [B,H,N,D]
+ *   N       tokens as allocated (any positive count)
+ *   D       head dimension, 64 or 128
+ *   kv_len  valid tokens, 1..N, a prefix of the sequence: keys >= kv_len are
+ *           ignored, query rows >= kv_len produce 0
+ *   scale   softmax scale; <= 0 selects 1/sqrt(D)
+ *   workspace, workspace_bytes   unused by the dense path; may be NULL / 0
+ *   stream  hipStream_t, NULL = default stream
+ * Returns RAPID_OK or a negative rapid_status.
+ */
+RAPID_API int rapid_attn_dense(const void* q, const void* k, const void* v, void* o,
+                     int B, int H, int N, int D, int kv_len, float scale,
+                     void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Block-sparse joint attention (Sec. 3.2 Level-3, Eq. 4; actions 1..N_sparse).
+ *   block   square mask tile edge in tokens, 64 or 128; N % block == 0
+ *   mask    device, uint8 [B,H,N/block,N/block], row-major (query-block,
+ *           key-block); nonzero = keep the tile.  One mask per (sample, head),
+ *           as the sparsity control is per layer and per head.
+ *   workspace  device scratch of at least rapid_attn_workspace_bytes(...)
+ *           bytes, 16-byte aligned.  The call first compacts the mask into
+ *           it, then runs attention over the kept tiles only:
+ *             int32 counts [B*H*nb]      kept key-blocks of each query-block
+ *                                        (blocks starting at or beyond kv_len
+ *                                        are dropped)
+ *             int32 order  [B*H*nb]      launch order of the query-blocks
+ *             int32 index  [B*H*nb*nb]   ascending kept key-blocks, row-wise;
+ *                                        entries past counts[] are undefined
+ *           (nb = N/block).  Contents are outputs of the call; the layout is
+ *           stated so tests can check the compaction bit-for-bit.
+ *   other arguments as rapid_attn_dense.
+ */
+RAPID_API int rapid_attn_block_sparse(const void* q, const void* k, const void* v, void* o,
+                            int B, int H, int N, int D, int block,
+                            const unsigned char* mask, int kv_len, float scale,
+                            void* workspace, size_t workspace_bytes, void* stream);
+
+/* Bytes of workspace rapid_attn_block_sparse needs for this shape; 0 if the
+ * shape is invalid or unsupported.  Pure host arithmetic. */
+RAPID_API size_t rapid_attn_workspace_bytes(int B, int H, int N, int D, int block);
+
+/* Static, NUL-terminated description of a status code.  Never NULL. */
+RAPID_API const char* rapid_attn_status_string(int status);
+
+/* RAPID_ATTN_VERSION the library was built from. */
+RAPID_API int rapid_attn_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* RAPID_ATTN_H */

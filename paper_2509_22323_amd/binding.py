@@ -1,0 +1,135 @@
+"""ctypes binding of librapid_attn.so: same names as the C ABI, marshalling only.
+
+PyTorch is used for device memory and streams, nothing else: tensors are passed as
+raw device pointers, kernels go to torch's current HIP stream.  There is no fallback:
+if the shared library is missing the first call raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SO = os.path.join(_HERE, "librapid_attn.so")
+_lib = None
+
+STATUS = {
+    "RAPID_OK": 0, "RAPID_ERR_NULL": -1, "RAPID_ERR_SHAPE": -2, "RAPID_ERR_UNSUPPORTED": -3,
+    "RAPID_ERR_ALIGN": -4, "RAPID_ERR_WORKSPACE": -5, "RAPID_ERR_DEVICE": -6,
+}
+
+EXPORTS = ("rapid_attn_dense", "rapid_attn_block_sparse", "rapid_attn_workspace_bytes",
+           "rapid_attn_status_string", "rapid_attn_version")
+
+
+class RapidAttnError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"rapid_attn status {status}: {message}")
+        self.status = status
+
+
+def library_path() -> str:
+    return _SO
+
+
+def _load_hip_runtime():
+    """librapid_attn.so is linked WITHOUT a HIP runtime of its own, so that its
+    launches go to the runtime that owns the caller's streams and allocations.
+    With PyTorch that is the libamdhip64.so bundled in torch/lib: make its symbols
+    global before the library (whose constructor registers the kernels) is opened."""
+    import torch
+    bundled = os.path.join(os.path.dirname(torch.__file__), "lib", "libamdhip64.so")
+    ctypes.CDLL(bundled if os.path.exists(bundled) else "libamdhip64.so", mode=ctypes.RTLD_GLOBAL)
+
+
+def library():
+    """The loaded C library with argtypes set.  Raises if it has not been built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_SO):
+        raise ImportError(
+            f"{_SO} is missing: build it first (python -c 'import __graft_entry__ as g; g.build()' "
+            "or python paper_2509_22323_amd/build.py). There is no CPU fallback.")
+    _load_hip_runtime()
+    lib = ctypes.CDLL(_SO)
+    vp, ci, cf, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_float, ctypes.c_size_t
+    lib.rapid_attn_dense.argtypes = [vp, vp, vp, vp, ci, ci, ci, ci, ci, cf, vp, sz, vp]
+    lib.rapid_attn_dense.restype = ci
+    lib.rapid_attn_block_sparse.argtypes = [vp, vp, vp, vp, ci, ci, ci, ci, ci, vp, ci, cf, vp, sz, vp]
+    lib.rapid_attn_block_sparse.restype = ci
+    lib.rapid_attn_workspace_bytes.argtypes = [ci, ci, ci, ci, ci]
+    lib.rapid_attn_workspace_bytes.restype = sz
+    lib.rapid_attn_status_string.argtypes = [ci]
+    lib.rapid_attn_status_string.restype = ctypes.c_char_p
+    lib.rapid_attn_version.argtypes = []
+    lib.rapid_attn_version.restype = ci
+    _lib = lib
+    return lib
+
+
+def rapid_attn_status_string(status: int) -> str:
+    return library().rapid_attn_status_string(int(status)).decode()
+
+
+def rapid_attn_version() -> int:
+    return library().rapid_attn_version()
+
+
+def rapid_attn_workspace_bytes(B: int, H: int, N: int, D: int, block: int) -> int:
+    return int(library().rapid_attn_workspace_bytes(B, H, N, D, block))
+
+
+def _check(status: int):
+    if status != 0:
+        raise RapidAttnError(status, rapid_attn_status_string(status))
+
+
+def _qkvo(q, k, v, o):
+    import torch
+    for name, t in (("q", q), ("k", k), ("v", v), ("o", o)):
+        if not (isinstance(t, torch.Tensor) and t.is_cuda and t.dtype == torch.bfloat16
+                and t.dim() == 4 and t.is_contiguous()):
+            raise TypeError(f"{name} must be a contiguous CUDA bfloat16 tensor [B,H,N,D]")
+        if t.shape != q.shape or t.device != q.device:
+            raise ValueError(f"{name} shape/device differs from q")
+    return tuple(int(s) for s in q.shape)
+
+
+def _stream(t):
+    import torch
+    return ctypes.c_void_p(torch.cuda.current_stream(t.device).cuda_stream)
+
+
+def rapid_attn_dense(q, k, v, o, kv_len=None, scale=0.0):
+    """o <- softmax(scale q k^T) v over the first kv_len tokens (all heads, samples).
+    Tensors: CUDA bf16 [B,H,N,D], contiguous.  Enqueued on torch's current stream."""
+    B, H, N, D = _qkvo(q, k, v, o)
+    kv_len = N if kv_len is None else int(kv_len)
+    _check(library().rapid_attn_dense(q.data_ptr(), k.data_ptr(), v.data_ptr(), o.data_ptr(),
+                                      B, H, N, D, kv_len, float(scale), None, 0, _stream(q)))
+    return o
+
+
+def rapid_attn_block_sparse(q, k, v, o, mask, block, kv_len=None, scale=0.0, workspace=None):
+    """As rapid_attn_dense, restricted to the tiles kept by `mask` (CUDA uint8
+    [B,H,N/block,N/block]).  `workspace`: CUDA uint8 tensor of at least
+    rapid_attn_workspace_bytes(...) bytes; allocated with torch if None.  Returns o."""
+    import torch
+    B, H, N, D = _qkvo(q, k, v, o)
+    kv_len = N if kv_len is None else int(kv_len)
+    if not (isinstance(mask, torch.Tensor) and mask.is_cuda and mask.dtype == torch.uint8
+            and mask.is_contiguous() and mask.device == q.device):
+        raise TypeError("mask must be a contiguous CUDA uint8 tensor")
+    if block > 0 and N % block == 0 and tuple(mask.shape) != (B, H, N // block, N // block):
+        raise ValueError(f"mask shape {tuple(mask.shape)} != {(B, H, N // block, N // block)}")
+    if workspace is None:
+        need = rapid_attn_workspace_bytes(B, H, N, D, int(block))
+        workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=q.device)
+    if not (workspace.is_cuda and workspace.is_contiguous() and workspace.device == q.device):
+        raise TypeError("workspace must be a contiguous CUDA tensor on q's device")
+    ws_bytes = workspace.numel() * workspace.element_size()
+    _check(library().rapid_attn_block_sparse(
+        q.data_ptr(), k.data_ptr(), v.data_ptr(), o.data_ptr(), B, H, N, D, int(block),
+        mask.data_ptr(), kv_len, float(scale), workspace.data_ptr(), ws_bytes, _stream(q)))
+    return o

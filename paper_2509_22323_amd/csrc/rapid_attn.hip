@@ -1,0 +1,422 @@
+// MM-DiT joint attention for MI355X (gfx950): dense and block-sparse, flash-style.
+//
+// Operation: RAPID^3 Sec. 3.1 Eq. 1 (self-attention block of a DiT layer) and
+// Sec. 3.2 Level-3 / Eq. 4 (the same block restricted to a pruned attention map,
+// per layer and per head).  The pruned map is given as a block mask; pruned tiles
+// are never read.
+//
+// Kernel shape.  One workgroup owns one query tile of 32*NW rows (NW wavefronts,
+// 32 query rows each) of one (sample, head) and walks over 64-key tiles:
+//   S^T = K Q^T    v_mfma_f32_32x32x16_bf16, A = K tile rows from LDS (128-bit
+//                  reads), B = the wave's Q rows held in registers for the whole
+//                  kernel.  Computing the TRANSPOSED score tile puts one query
+//                  per lane: the running max / sum are per-lane scalars, the row
+//                  reductions are in-register plus ONE cross-half exchange
+//                  (v_permlane32_swap), and the fp32 accumulator registers of a
+//                  lane are, after conversion to bf16, exactly the B operand of
+//                  the next product -- P never touches LDS.
+//   O^T += V^T P^T same MFMA; A = V^T fragments fetched straight out of the
+//                  row-major V tile with the LDS transpose read
+//                  (ds_read_b64_tr_b16), B = P^T from the registers above.
+// The contraction index of the second product is a dummy, so its key order
+// inside a 16-key step is whatever the accumulator layout yields (keys
+// 4h+r and 8+4h+r for lane half h); the V^T fragments are fetched in that order.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "rapid_attn.h"
+
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int KT = 64;          // keys per LDS tile
+constexpr int XCDS = 8;         // L2 domains the dispatcher deals workgroups over
+constexpr float LOG2E = 1.44269504088896340736f;
+
+#define LDS_PTR(T, p) ((__attribute__((address_space(3))) T*)(p))
+
+struct AttnParams {
+    const __bf16* q;
+    const __bf16* k;
+    const __bf16* v;
+    __bf16* o;
+    const int32_t* counts;   // sparse: kept key-blocks per (b,h,query-block); dense: null
+    const int32_t* order;    // sparse: launch order of (b,h,query-block) items
+    const int32_t* index;    // sparse: kept key-block lists, nb per row
+    int H, N, kv_len;
+    int nq;                  // query tiles per (sample, head)
+    int items;               // B*H*nq
+    int chunk;               // ceil(items / XCDS)
+    int block, nb;           // mask tile edge, N / block (sparse only)
+    float c;                 // scale * log2(e)
+};
+
+// ---------------------------------------------------------------------------
+// Mask compaction: one wavefront per (b, h, query-block) row of the mask.
+// counts[row] = number of kept key-blocks whose first token is below kv_len;
+// index[row*nb + 0..count) = those key-blocks, ascending; order[row] = row.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void compact_mask_kernel(
+    const unsigned char* __restrict__ mask, int rows, int nb, int block, int kv_len,
+    int32_t* __restrict__ counts, int32_t* __restrict__ order, int32_t* __restrict__ index)
+{
+    const int lane = threadIdx.x & 63;
+    const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (row >= rows) return;
+    const unsigned char* mrow = mask + (size_t)row * nb;
+    int32_t* irow = index + (size_t)row * nb;
+    int base = 0;
+    for (int j0 = 0; j0 < nb; j0 += 64) {
+        const int j = j0 + lane;
+        const bool keep = (j < nb) && (mrow[j] != 0) && ((long long)j * block < kv_len);
+        const unsigned long long bal = __ballot(keep);
+        if (keep) irow[base + __popcll(bal & ((1ull << lane) - 1ull))] = j;
+        base += __popcll(bal);
+    }
+    if (lane == 0) { counts[row] = base; order[row] = row; }
+}
+
+// ---------------------------------------------------------------------------
+// Attention.  D in {64,128}; NW wavefronts; query tile = 32*NW rows.
+// ---------------------------------------------------------------------------
+template <int D>
+struct Tile {
+    static constexpr int LDK = D + 8;             // bf16 elements per LDS row (16-byte pad)
+    static constexpr int CHUNKS = KT * D / 8;     // 16-byte chunks per K (or V) tile
+};
+
+// Stage one 64 x D tile (rows key0 .. key0+63 of `src`) into LDS; rows at or beyond
+// kv_len become zeros, so NaN/Inf in the padding can never reach an MFMA.
+template <int D, int NT>
+__device__ __forceinline__ void stage_tile(const __bf16* __restrict__ src, int key0, int kv_len,
+                                           __bf16* lds, int tid)
+{
+    constexpr int CPR = D / 8;                    // chunks per row
+    constexpr int LDK = Tile<D>::LDK;
+#pragma unroll
+    for (int c = tid; c < Tile<D>::CHUNKS; c += NT) {
+        const int row = c / CPR, col = (c % CPR) * 8;
+        u32x4 val = {0u, 0u, 0u, 0u};
+        if (key0 + row < kv_len)
+            val = *(const u32x4*)(src + (size_t)(key0 + row) * D + col);
+        *(u32x4*)(lds + row * LDK + col) = val;
+    }
+}
+
+template <int D, int NW>
+__global__ __launch_bounds__(64 * NW) void attn_kernel(const AttnParams p)
+{
+    constexpr int NT = 64 * NW;
+    constexpr int QT = 32 * NW;
+    constexpr int LDK = Tile<D>::LDK;
+    constexpr int KS = D / 16;                    // k-steps of the QK^T product
+    constexpr int DB = D / 32;                    // 32-row blocks of O^T
+
+    __shared__ __attribute__((aligned(16))) __bf16 lds_k[KT * LDK];
+    __shared__ __attribute__((aligned(16))) __bf16 lds_v[KT * LDK];
+
+    // XCD-aware work mapping: the dispatcher deals consecutive workgroup ids
+    // round-robin over the 8 XCDs, so give each XCD a contiguous run of items
+    // (query tiles of the same head share K/V in that XCD's L2).
+    const int wg = blockIdx.x;
+    int item = (wg % XCDS) * p.chunk + wg / XCDS;
+    if (item >= p.items) return;
+    if (p.order) item = p.order[item];
+    const int bh = item / p.nq;
+    const int qi = item % p.nq;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int n = lane & 31;                      // query within the wave / MFMA column
+    const int h = lane >> 5;                      // lane half
+    const int kv_len = p.kv_len;
+
+    const size_t base = (size_t)bh * p.N * D;
+    const __bf16* __restrict__ Q = p.q + base;
+    const __bf16* __restrict__ K = p.k + base;
+    const __bf16* __restrict__ V = p.v + base;
+    __bf16* __restrict__ O = p.o + base;
+
+    const int qrow = qi * QT + wave * 32 + n;     // this lane's query row
+    const bool qvalid = qrow < kv_len;            // kv_len <= N
+
+    // Q^T fragments (B operand): lane (n, h) holds Q[qrow][16t + 8h .. +8].
+    bf16x8 qf[KS];
+#pragma unroll
+    for (int t = 0; t < KS; ++t) {
+        u32x4 raw = {0u, 0u, 0u, 0u};
+        if (qvalid) raw = *(const u32x4*)(Q + (size_t)qrow * D + 16 * t + 8 * h);
+        qf[t] = __builtin_bit_cast(bf16x8, raw);
+    }
+
+    f32x16 acc[DB];
+#pragma unroll
+    for (int i = 0; i < DB; ++i)
+#pragma unroll
+        for (int j = 0; j < 16; ++j) acc[i][j] = 0.f;
+    float m_run = -INFINITY;                      // running max of raw scores (shared by both halves)
+    float l_run = 0.f;                            // this lane's partial running sum
+
+    // key tiles to visit
+    const int sub = p.counts ? p.block / KT : 1;  // 64-key tiles per mask block
+    const int n_blocks = p.counts ? p.counts[item] : (kv_len + KT - 1) / KT;
+    const int32_t* list = p.counts ? p.index + (size_t)item * p.nb : nullptr;
+
+    // per-lane offsets of the transpose read: within a 16-lane group, lane j points
+    // at row j/4, columns 4*(j%4)..+3 of a 4 x 16 patch; lane i receives column i.
+    const int tr_row = (lane & 15) >> 2;
+    const int tr_col = ((lane & 3) << 2) + (((lane >> 4) & 1) << 4);
+
+    for (int bi = 0; bi < n_blocks; ++bi) {
+        const int blk = list ? list[bi] : bi;
+        for (int s = 0; s < sub; ++s) {
+            const int key0 = (blk * sub + s) * KT;
+            if (key0 >= kv_len) break;            // uniform over the workgroup
+
+            __syncthreads();                      // everyone is done reading the previous tile
+            stage_tile<D, NT>(K, key0, kv_len, lds_k, tid);
+            stage_tile<D, NT>(V, key0, kv_len, lds_v, tid);
+            __syncthreads();
+
+            // ---- S^T = K Q^T : two 32-key row blocks
+            f32x16 st[2];
+#pragma unroll
+            for (int rb = 0; rb < 2; ++rb) {
+#pragma unroll
+                for (int j = 0; j < 16; ++j) st[rb][j] = 0.f;
+#pragma unroll
+                for (int t = 0; t < KS; ++t) {
+                    const bf16x8 a = *(const bf16x8*)(lds_k + (rb * 32 + n) * LDK + 16 * t + 8 * h);
+                    st[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[t], st[rb], 0, 0, 0);
+                }
+            }
+            // register i of row block rb holds key  key0 + 32 rb + 8 (i/4) + 4 h + i%4
+            if (key0 + KT > kv_len) {
+#pragma unroll
+                for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) {
+                        const int key = key0 + 32 * rb + 8 * (i >> 2) + 4 * h + (i & 3);
+                        if (key >= kv_len) st[rb][i] = -INFINITY;
+                    }
+            }
+
+            // ---- online softmax (one query per lane; halves hold disjoint keys)
+            float mx = st[0][0];
+#pragma unroll
+            for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) mx = fmaxf(mx, st[rb][i]);
+            {
+                auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(mx), __float_as_uint(mx), false, false);
+                mx = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
+            }
+            const float m_new = fmaxf(m_run, mx);     // finite: every visited tile has a valid key
+            const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * p.c);
+            const float mc = m_new * p.c;
+            m_run = m_new;
+            float rs = 0.f;
+#pragma unroll
+            for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    const float e = __builtin_amdgcn_exp2f(__builtin_fmaf(st[rb][i], p.c, -mc));
+                    st[rb][i] = e;
+                    rs += e;
+                }
+            l_run = l_run * alpha + rs;
+#pragma unroll
+            for (int i = 0; i < DB; ++i)
+#pragma unroll
+                for (int j = 0; j < 16; ++j) acc[i][j] *= alpha;
+
+            // ---- O^T += V^T P^T
+#pragma unroll
+            for (int rb = 0; rb < 2; ++rb) {
+#pragma unroll
+                for (int t = 0; t < 2; ++t) {
+                    bf16x8 pb;                        // keys 16t + {4h..4h+3, 8+4h..8+4h+3} of row block rb
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) pb[i] = (__bf16)st[rb][8 * t + i];
+                    const __bf16* vrow = lds_v + (rb * 32 + 16 * t + 4 * h + tr_row) * LDK + tr_col;
+#pragma unroll
+                    for (int db = 0; db < DB; ++db) {
+                        const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, vrow + db * 32));
+                        const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, vrow + 8 * LDK + db * 32));
+                        const s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+                        acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                            __builtin_bit_cast(bf16x8, both), pb, acc[db], 0, 0, 0);
+                    }
+                }
+            }
+        }
+    }
+
+    // ---- epilogue: O = acc / l ; register 4j+r of block db holds d = 32 db + 8 j + 4 h + r
+    {
+        auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(l_run), __float_as_uint(l_run), false, false);
+        l_run = __uint_as_float(sw[0]) + __uint_as_float(sw[1]);
+    }
+    const float inv = (qvalid && l_run > 0.f) ? 1.0f / l_run : 0.f;
+    if (qrow < p.N) {
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                bf16x4 ov;
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const float x = acc[db][4 * j + r] * inv;
+                    ov[r] = (__bf16)((inv != 0.f) ? x : 0.f);
+                }
+                *(bf16x4*)(O + (size_t)qrow * D + 32 * db + 8 * j + 4 * h) = ov;
+            }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Host side
+// ---------------------------------------------------------------------------
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+struct WorkspaceLayout {
+    size_t counts_off, order_off, index_off, total;
+};
+
+inline WorkspaceLayout workspace_layout(int B, int H, int nb)
+{
+    const size_t rows = (size_t)B * H * nb;
+    auto up = [](size_t x) { return (x + 255) & ~(size_t)255; };
+    WorkspaceLayout w;
+    w.counts_off = 0;
+    w.order_off = up(rows * 4);
+    w.index_off = w.order_off + up(rows * 4);
+    w.total = w.index_off + up(rows * (size_t)nb * 4);
+    return w;
+}
+
+int check_common(const void* q, const void* k, const void* v, const void* o,
+                 int B, int H, int N, int D, int kv_len)
+{
+    if (!q || !k || !v || !o) return RAPID_ERR_NULL;
+    if (B <= 0 || H <= 0 || N <= 0) return RAPID_ERR_SHAPE;
+    if (kv_len < 1 || kv_len > N) return RAPID_ERR_SHAPE;
+    if ((long long)B * H > 0x7fffffffLL / 4096) return RAPID_ERR_SHAPE;
+    if (N > (1 << 22)) return RAPID_ERR_SHAPE;
+    if (D != 64 && D != 128) return RAPID_ERR_UNSUPPORTED;
+    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o)) return RAPID_ERR_ALIGN;
+    return RAPID_OK;
+}
+
+template <int D, int NW>
+int launch_attn(const AttnParams& p, hipStream_t stream)
+{
+    const int grid = p.chunk * XCDS;
+    hipLaunchKernelGGL((attn_kernel<D, NW>), dim3(grid), dim3(64 * NW), 0, stream, p);
+    return hipGetLastError() == hipSuccess ? RAPID_OK : RAPID_ERR_DEVICE;
+}
+
+}  // namespace
+
+extern "C" {
+
+int rapid_attn_dense(const void* q, const void* k, const void* v, void* o,
+                     int B, int H, int N, int D, int kv_len, float scale,
+                     void* workspace, size_t workspace_bytes, void* stream)
+{
+    (void)workspace; (void)workspace_bytes;
+    const int rc = check_common(q, k, v, o, B, H, N, D, kv_len);
+    if (rc != RAPID_OK) return rc;
+    if (!(scale > 0.f)) scale = 1.0f / sqrtf((float)D);
+
+    AttnParams p{};
+    p.q = (const __bf16*)q; p.k = (const __bf16*)k; p.v = (const __bf16*)v; p.o = (__bf16*)o;
+    p.counts = nullptr; p.order = nullptr; p.index = nullptr;
+    p.H = H; p.N = N; p.kv_len = kv_len;
+    p.nq = (N + 127) / 128;
+    const long long items = (long long)B * H * p.nq;
+    if (items > 0x7fffffffLL / 2) return RAPID_ERR_SHAPE;
+    p.items = (int)items;
+    p.chunk = (p.items + XCDS - 1) / XCDS;
+    p.block = 0; p.nb = 0;
+    p.c = scale * LOG2E;
+    hipStream_t s = (hipStream_t)stream;
+    return D == 64 ? launch_attn<64, 4>(p, s) : launch_attn<128, 4>(p, s);
+}
+
+int rapid_attn_block_sparse(const void* q, const void* k, const void* v, void* o,
+                            int B, int H, int N, int D, int block,
+                            const unsigned char* mask, int kv_len, float scale,
+                            void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (!mask) return RAPID_ERR_NULL;
+    int rc = check_common(q, k, v, o, B, H, N, D, kv_len);
+    if (rc != RAPID_OK) return rc;
+    if (block != 64 && block != 128) return RAPID_ERR_UNSUPPORTED;
+    if (N % block != 0) return RAPID_ERR_SHAPE;
+    const int nb = N / block;
+    const long long rows = (long long)B * H * nb;
+    if (rows > 0x7fffffffLL / 2) return RAPID_ERR_SHAPE;
+    const WorkspaceLayout w = workspace_layout(B, H, nb);
+    if (!workspace || workspace_bytes < w.total) return RAPID_ERR_WORKSPACE;
+    if (!aligned16(workspace)) return RAPID_ERR_ALIGN;
+    if (!(scale > 0.f)) scale = 1.0f / sqrtf((float)D);
+
+    char* ws = (char*)workspace;
+    int32_t* counts = (int32_t*)(ws + w.counts_off);
+    int32_t* order = (int32_t*)(ws + w.order_off);
+    int32_t* index = (int32_t*)(ws + w.index_off);
+    hipStream_t s = (hipStream_t)stream;
+
+    hipLaunchKernelGGL(compact_mask_kernel, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, s,
+                       mask, (int)rows, nb, block, kv_len, counts, order, index);
+    if (hipGetLastError() != hipSuccess) return RAPID_ERR_DEVICE;
+
+    AttnParams p{};
+    p.q = (const __bf16*)q; p.k = (const __bf16*)k; p.v = (const __bf16*)v; p.o = (__bf16*)o;
+    p.counts = counts; p.order = order; p.index = index;
+    p.H = H; p.N = N; p.kv_len = kv_len;
+    p.nq = nb;
+    p.items = (int)rows;
+    p.chunk = (p.items + XCDS - 1) / XCDS;
+    p.block = block; p.nb = nb;
+    p.c = scale * LOG2E;
+    if (block == 128)
+        return D == 64 ? launch_attn<64, 4>(p, s) : launch_attn<128, 4>(p, s);
+    return D == 64 ? launch_attn<64, 2>(p, s) : launch_attn<128, 2>(p, s);
+}
+
+size_t rapid_attn_workspace_bytes(int B, int H, int N, int D, int block)
+{
+    if (B <= 0 || H <= 0 || N <= 0) return 0;
+    if (D != 64 && D != 128) return 0;
+    if (block != 64 && block != 128) return 0;
+    if (N % block != 0 || N > (1 << 22)) return 0;
+    if ((long long)B * H * (N / block) > 0x7fffffffLL / 2) return 0;
+    return workspace_layout(B, H, N / block).total;
+}
+
+const char* rapid_attn_status_string(int status)
+{
+    switch (status) {
+        case RAPID_OK: return "ok";
+        case RAPID_ERR_NULL: return "a required pointer is NULL";
+        case RAPID_ERR_SHAPE: return "invalid shape: need B,H,N > 0, 1 <= kv_len <= N, N % block == 0";
+        case RAPID_ERR_UNSUPPORTED: return "unsupported: D must be 64 or 128, block must be 64 or 128";
+        case RAPID_ERR_ALIGN: return "q/k/v/o/workspace must be 16-byte aligned";
+        case RAPID_ERR_WORKSPACE: return "workspace is NULL or smaller than rapid_attn_workspace_bytes()";
+        case RAPID_ERR_DEVICE: return "HIP runtime refused the launch";
+        default: return "unknown status";
+    }
+}
+
+int rapid_attn_version(void) { return RAPID_ATTN_VERSION; }
+
+}  // extern "C"

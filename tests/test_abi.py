@@ -1,0 +1,111 @@
+"""Host-only checks of the C ABI: the library loads without a GPU, exports every
+symbol the header declares, and every argument error is reported before any launch."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2509_22323_amd as ra
+from paper_2509_22323_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = open(os.path.join(ROOT, "include", "rapid_attn.h")).read()
+
+
+def declared_symbols():
+    return re.findall(r"RAPID_API\s+[\w\s\*]+?\b(rapid_attn_\w+)\s*\(", HEADER)
+
+
+def test_header_declares_the_expected_entry_points():
+    assert set(declared_symbols()) == set(binding.EXPORTS)
+
+
+def test_library_exports_every_declared_symbol():
+    ra.library()                                  # brings in the HIP runtime it binds to
+    lib = ctypes.CDLL(ra.library_path())
+    for name in declared_symbols():
+        assert hasattr(lib, name), name
+
+
+def test_version_and_status_strings():
+    assert ra.rapid_attn_version() == int(re.search(r"#define RAPID_ATTN_VERSION (\d+)", HEADER).group(1))
+    for name, code in ra.STATUS.items():
+        assert re.search(rf"{name}\s*=\s*{code}\b", HEADER), name
+        assert ra.rapid_attn_status_string(code) not in ("", "unknown status")
+    assert ra.rapid_attn_status_string(12345) == "unknown status"
+
+
+def test_workspace_bytes():
+    f = ra.rapid_attn_workspace_bytes
+    nb = 36
+    rows = 24 * nb
+    need = f(1, 24, 4608, 128, 128)
+    assert need >= rows * 4 * 2 + rows * nb * 4 and need % 256 == 0
+    assert f(8, 24, 4480, 64, 128) > f(1, 24, 4480, 64, 128)
+    assert f(1, 2, 256, 64, 64) > 0
+    for bad in [(0, 1, 128, 64, 64), (1, 0, 128, 64, 64), (1, 1, 0, 64, 64), (1, 1, 128, 32, 64),
+                (1, 1, 128, 64, 32), (1, 1, 192, 64, 128), (1, 1, 128, 64, 0)]:
+        assert f(*bad) == 0, bad
+
+
+A = 0x10000          # fake, 16-byte aligned "device" addresses: never dereferenced,
+WS = 0x7000000       # every call below must fail validation before any launch
+
+
+def dense(q=A, k=A + 0x100000, v=A + 0x200000, o=A + 0x300000, B=1, H=2, N=256, D=64,
+          kv_len=256, scale=0.0):
+    return ra.library().rapid_attn_dense(q, k, v, o, B, H, N, D, kv_len, scale, None, 0, None)
+
+
+def sparse(q=A, k=A + 0x100000, v=A + 0x200000, o=A + 0x300000, B=1, H=2, N=256, D=64, block=64,
+           mask=A + 0x400000, kv_len=256, scale=0.0, ws=WS, ws_bytes=1 << 20):
+    return ra.library().rapid_attn_block_sparse(q, k, v, o, B, H, N, D, block, mask, kv_len, scale,
+                                                ws, ws_bytes, None)
+
+
+S = ra.STATUS
+
+
+@pytest.mark.parametrize("kw,code", [
+    (dict(q=None), "RAPID_ERR_NULL"), (dict(k=None), "RAPID_ERR_NULL"),
+    (dict(v=None), "RAPID_ERR_NULL"), (dict(o=None), "RAPID_ERR_NULL"),
+    (dict(B=0), "RAPID_ERR_SHAPE"), (dict(H=-1), "RAPID_ERR_SHAPE"), (dict(N=0), "RAPID_ERR_SHAPE"),
+    (dict(kv_len=0), "RAPID_ERR_SHAPE"), (dict(kv_len=257), "RAPID_ERR_SHAPE"),
+    (dict(D=96), "RAPID_ERR_UNSUPPORTED"), (dict(D=256), "RAPID_ERR_UNSUPPORTED"),
+    (dict(q=A + 8), "RAPID_ERR_ALIGN"), (dict(o=A + 0x300002), "RAPID_ERR_ALIGN"),
+])
+def test_dense_argument_errors(kw, code):
+    assert dense(**kw) == S[code]
+
+
+@pytest.mark.parametrize("kw,code", [
+    (dict(mask=None), "RAPID_ERR_NULL"), (dict(v=None), "RAPID_ERR_NULL"),
+    (dict(B=0), "RAPID_ERR_SHAPE"), (dict(kv_len=300), "RAPID_ERR_SHAPE"),
+    (dict(N=320, kv_len=300, block=128), "RAPID_ERR_SHAPE"),
+    (dict(block=32), "RAPID_ERR_UNSUPPORTED"), (dict(block=256), "RAPID_ERR_UNSUPPORTED"),
+    (dict(D=80), "RAPID_ERR_UNSUPPORTED"),
+    (dict(k=A + 0x100004), "RAPID_ERR_ALIGN"), (dict(ws=WS + 4), "RAPID_ERR_ALIGN"),
+    (dict(ws=None), "RAPID_ERR_WORKSPACE"), (dict(ws_bytes=0), "RAPID_ERR_WORKSPACE"),
+    (dict(ws_bytes=ra.rapid_attn_workspace_bytes(1, 2, 256, 64, 64) - 1), "RAPID_ERR_WORKSPACE"),
+])
+def test_sparse_argument_errors(kw, code):
+    assert sparse(**kw) == S[code]
+
+
+def test_binding_rejects_non_tensors_and_raises_on_status():
+    with pytest.raises(TypeError):
+        ra.rapid_attn_dense(1, 2, 3, 4)
+    err = ra.RapidAttnError(-2, ra.rapid_attn_status_string(-2))
+    assert err.status == -2 and "shape" in str(err)
+
+
+def test_product_package_does_not_touch_the_oracle():
+    pkg = os.path.join(ROOT, "paper_2509_22323_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".h", ".cpp")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert "oracle" not in text.lower(), f
+    orc = open(os.path.join(ROOT, "oracle", "__init__.py")).read()
+    assert "paper_2509_22323_amd" not in orc

@@ -1,0 +1,141 @@
+"""GPU parity: the HIP path (through the C ABI) against the fp64 oracle, element by
+element on the same seeded inputs.  Tolerances: max-abs 1e-2, mean-abs 1e-3, plus a
+relative Frobenius bound of 1e-2; integer work (mask compaction) is bit-exact."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2509_22323_amd as ra
+import workloads as wl
+from gpu_common import assert_close, from_dev, to_dev, widen
+
+pytestmark = pytest.mark.gpu
+
+
+def run_dense(q, k, v, kv_len, scale=0.0):
+    dq, dk, dv = to_dev(q), to_dev(k), to_dev(v)
+    o = torch.full_like(dq, float("nan"))
+    ra.rapid_attn_dense(dq, dk, dv, o, kv_len, scale)
+    torch.cuda.synchronize()
+    return from_dev(o)
+
+
+def run_sparse(q, k, v, mask, block, kv_len, scale=0.0, return_ws=False):
+    dq, dk, dv = to_dev(q), to_dev(k), to_dev(v)
+    dm = torch.from_numpy(mask).cuda()
+    B, H, N, D = q.shape
+    ws = torch.full((ra.rapid_attn_workspace_bytes(B, H, N, D, block),), 0xAB, dtype=torch.uint8, device="cuda")
+    o = torch.full_like(dq, float("nan"))
+    ra.rapid_attn_block_sparse(dq, dk, dv, o, dm, block, kv_len, scale, ws)
+    torch.cuda.synchronize()
+    return (from_dev(o), ws.cpu().numpy()) if return_ws else from_dev(o)
+
+
+# ---------------------------------------------------------------- small, every element
+SMALL = [
+    # B, H, N, D, block, kv_len, p_keep, pad_fill
+    (1, 2, 256, 64, 64, 256, 0.5, "zero"),      # the Tiny workload's shape
+    (2, 3, 384, 64, 64, 300, 0.4, "nan"),       # ragged tail inside a tile, several tiles
+    (1, 2, 512, 128, 128, 512, 0.5, "zero"),
+    (2, 2, 384, 128, 128, 333, 0.5, "nan"),
+    (1, 3, 640, 64, 128, 577, 0.3, "inf"),
+    (1, 2, 320, 128, 64, 259, 0.5, "nan"),
+    (3, 1, 128, 64, 64, 1, 1.0, "nan"),         # a single valid token
+    (1, 1, 1152, 128, 128, 1100, 0.35, "nan"),
+]
+
+
+@pytest.mark.parametrize("B,H,N,D,block,kv_len,p,fill", SMALL)
+def test_dense_small(B, H, N, D, block, kv_len, p, fill):
+    q, k, v = wl.make_qkv(B, H, N, D, kv_len, seed=101, pad_fill=fill)
+    got = run_dense(q, k, v, kv_len)
+    ref = oracle.attention(q, k, v, kv_len)
+    assert_close(got, ref, "dense")
+    assert (got[:, :, kv_len:] == 0).all()
+
+
+@pytest.mark.parametrize("B,H,N,D,block,kv_len,p,fill", SMALL)
+def test_sparse_small(B, H, N, D, block, kv_len, p, fill):
+    q, k, v = wl.make_qkv(B, H, N, D, kv_len, seed=102, pad_fill=fill)
+    mask = wl.mask_bernoulli_diag(B, H, N // block, p, seed=7)
+    got = run_sparse(q, k, v, mask, block, kv_len)
+    ref = oracle.attention(q, k, v, kv_len, mask, block)
+    assert_close(got, ref, "sparse")
+    assert (got[:, :, kv_len:] == 0).all()
+
+
+@pytest.mark.parametrize("N,kv_len,D", [(200, 200, 64), (77, 50, 128), (130, 129, 64)])
+def test_dense_any_token_count(N, kv_len, D):
+    q, k, v = wl.make_qkv(2, 2, N, D, kv_len, seed=103, pad_fill="nan")
+    assert_close(run_dense(q, k, v, kv_len), oracle.attention(q, k, v, kv_len), "dense odd N")
+
+
+def test_tiny_workload_both_masks_and_dense():
+    w = wl.WORKLOADS["tiny"]
+    q, k, v = w.qkv()
+    ref_dense = oracle.attention(q, k, v, w.kv_len)
+    assert_close(run_dense(q, k, v, w.kv_len), ref_dense, "tiny dense")
+    assert_close(run_sparse(q, k, v, w.mask(1.0), w.block, w.kv_len), ref_dense, "tiny all-ones")
+    m = w.mask(0.5)
+    assert_close(run_sparse(q, k, v, m, w.block, w.kv_len),
+                 oracle.attention(q, k, v, w.kv_len, m, w.block), "tiny 0.5")
+
+
+def test_custom_scale_and_peaky_inputs():
+    B, H, N, D, kv_len = 1, 2, 384, 64, 350
+    q, k, v = wl.make_qkv(B, H, N, D, kv_len, seed=104)
+    assert_close(run_dense(q, k, v, kv_len, 0.31), oracle.attention(q, k, v, kv_len, scale=0.31), "scale")
+    # scores with std ~16: the running max moves a lot, probabilities are near one-hot
+    q, k, v = wl.make_qkv(B, H, N, D, kv_len, seed=105, gain=4.0)
+    ref = oracle.attention(q, k, v, kv_len)
+    got = widen(run_dense(q, k, v, kv_len))
+    assert np.isfinite(got).all()
+    # values are ~4x larger here: compare relative to the value scale
+    assert np.abs(got - ref).max() <= 4 * 1e-2 and np.abs(got - ref).mean() <= 4 * 1e-3
+
+
+def test_compaction_is_bit_exact():
+    B, H, N, D, block, kv_len = 2, 3, 1152, 64, 128, 1100
+    q, k, v = wl.make_qkv(B, H, N, D, kv_len, seed=106)
+    mask = wl.mask_bernoulli_diag(B, H, N // block, 0.4, seed=9)
+    mask[0, 0, 2, :] = 0                                   # an empty row
+    mask[1, 2, :, :] = 3                                   # nonzero, not 1
+    _, ws = run_sparse(q, k, v, mask, block, kv_len, return_ws=True)
+    nb = N // block
+    rows = B * H * nb
+    up = lambda x: (x + 255) // 256 * 256
+    counts = ws[:rows * 4].view(np.int32)
+    order = ws[up(rows * 4):up(rows * 4) + rows * 4].view(np.int32)
+    index = ws[2 * up(rows * 4):2 * up(rows * 4) + rows * nb * 4].view(np.int32).reshape(rows, nb)
+    want_counts, want_index = oracle.kept_tiles(mask, block, kv_len)
+    np.testing.assert_array_equal(counts, want_counts.reshape(-1))
+    assert sorted(order.tolist()) == list(range(rows))
+    want_index = want_index.reshape(rows, nb)
+    for r in range(rows):
+        np.testing.assert_array_equal(index[r, :counts[r]], want_index[r, :counts[r]])
+
+
+# ---------------------------------------------------------------- full sizes, sampled rows
+FULL = [("sd3_1024", 1.0), ("sd3_1024", 0.25), ("flux_1024", 1.0), ("flux_1024", 0.5),
+        ("flux_1024", 0.2), ("grpo_sd3", "mixed"), ("flux_2048", 0.1), ("flux_2048", 0.3)]
+
+
+@pytest.mark.parametrize("name,density", FULL)
+def test_full_size_sampled_rows(name, density):
+    """The bench's launch configuration at the full workload sizes; the oracle
+    computes a seeded sample of output rows (first/last/boundary/pad rows included)."""
+    w = wl.WORKLOADS[name]
+    q, k, v = w.qkv(pad_fill="nan")
+    mask = w.mask(density)
+    rows = wl.sample_rows(w.B, w.H, w.N, w.kv_len, w.block, 384, seed=w.seed() + 1)
+    got = run_sparse(q, k, v, mask, w.block, w.kv_len)
+    ref = oracle.attention_rows(q, k, v, rows, w.kv_len, mask, w.block)
+    sel = got[rows[:, 0], rows[:, 1], rows[:, 2]]
+    assert_close(sel, ref, f"{name} d={density} sparse entry")
+    assert (got[:, :, w.kv_len:] == 0).all()
+    assert np.isfinite(widen(got)).all()
+    if density == 1.0:
+        got_d = run_dense(q, k, v, w.kv_len)
+        assert_close(got_d[rows[:, 0], rows[:, 1], rows[:, 2]], ref, f"{name} dense entry")
+        np.testing.assert_array_equal(got_d, got)          # action 0 == all-ones mask
