@@ -89,8 +89,9 @@ RAPID_API int rapid_attn_dense(const void* q, const void* k, const void* v, void
  *             int32 order  [B*H*nb]      launch order of the query-blocks
  *             int32 index  [B*H*nb*nb]   ascending kept key-blocks, row-wise;
  *                                        entries past counts[] are undefined
- *           (nb = N/block).  Contents are outputs of the call; the layout is
- *           stated so tests can check the compaction bit-for-bit.
+ *           (nb = N/block).  Each array starts at the next 256-byte boundary
+ *           after the previous one.  Contents are outputs of the call; the
+ *           layout is stated so tests can check the compaction bit-for-bit.
  *   other arguments as rapid_attn_dense.
  */
 RAPID_API int rapid_attn_block_sparse(const void* q, const void* k, const void* v, void* o,
