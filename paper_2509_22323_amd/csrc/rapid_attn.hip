@@ -54,6 +54,7 @@ struct AttnParams {
     int items;               // B*H*nq
     int chunk;               // ceil(items / XCDS)
     int block, nb;           // mask tile edge, N / block (sparse only)
+    int sub_shift;           // log2(block / 64)
     float c;                 // scale * log2(e)
 };
 
@@ -85,41 +86,157 @@ __global__ __launch_bounds__(256) void compact_mask_kernel(
 // ---------------------------------------------------------------------------
 // Attention.  D in {64,128}; NW wavefronts; query tile = 32*NW rows.
 // ---------------------------------------------------------------------------
+// LDS tile geometry.  A 64 x D bf16 tile is stored row-major WITHOUT padding, because
+// it is filled by direct global->LDS loads (global_load_lds_dwordx4: one instruction
+// writes 64 lanes x 16 B = 1 KB of consecutive LDS).  Bank conflicts are avoided by
+// permuting the 16-byte chunks inside each row: physical chunk = logical chunk ^ swz(row).
+// The permutation is applied on the global side of the copy (each lane chooses which
+// chunk of the row it fetches), so the copy stays fully coalesced.
 template <int D>
-struct Tile {
-    static constexpr int LDK = D + 8;             // bf16 elements per LDS row (16-byte pad)
-    static constexpr int CHUNKS = KT * D / 8;     // 16-byte chunks per K (or V) tile
+struct Geo {
+    static constexpr int ROW_BYTES = D * 2;                 // 256 | 128
+    static constexpr int CPR = D / 8;                       // chunks per row: 16 | 8
+    static constexpr int TILE_BYTES = KT * ROW_BYTES;       // 16384 | 8192
+    static constexpr int ROWS_PER_LOAD = 1024 / ROW_BYTES;  // 4 | 8
+    static constexpr int LOADS = TILE_BYTES / 1024;         // 16 | 8
+    // K is read 16 bytes per lane, lanes = consecutive rows at one logical chunk:
+    // 16 consecutive rows must land on 16 different chunks of the 256-byte bank line.
+    static __device__ __forceinline__ int swz_k(int row) { return D == 128 ? (row & 15) : ((row >> 1) & 7); }
+    // V is read by the transpose read as 4-row x 64-byte patches: consecutive rows must
+    // land on different 64-byte groups of the bank line.
+    static __device__ __forceinline__ int swz_v(int row) { return D == 128 ? ((row & 3) << 2) : (((row >> 1) & 1) << 2); }
 };
 
-// Stage one 64 x D tile (rows key0 .. key0+63 of `src`) into LDS; rows at or beyond
-// kv_len become zeros, so NaN/Inf in the padding can never reach an MFMA.
-template <int D, int NT>
-__device__ __forceinline__ void stage_tile(const __bf16* __restrict__ src, int key0, int kv_len,
-                                           __bf16* lds, int tid)
+// Issue the asynchronous copy of rows key0..key0+63 of `src` into an LDS tile.  Rows at or
+// beyond kv_len are replaced by row kv_len-1 (finite data; their probabilities are exactly
+// 0, and their scores are overwritten with -inf, so they never contribute).
+template <int D, int NW, bool IS_V>
+__device__ __forceinline__ void issue_tile(const __bf16* __restrict__ src, int key0, int kv_len,
+                                           char* lds, int wave, int lane)
 {
-    constexpr int CPR = D / 8;                    // chunks per row
-    constexpr int LDK = Tile<D>::LDK;
+    typedef Geo<D> G;
+    constexpr int PER_WAVE = G::LOADS / NW;
 #pragma unroll
-    for (int c = tid; c < Tile<D>::CHUNKS; c += NT) {
-        const int row = c / CPR, col = (c % CPR) * 8;
-        u32x4 val = {0u, 0u, 0u, 0u};
-        if (key0 + row < kv_len)
-            val = *(const u32x4*)(src + (size_t)(key0 + row) * D + col);
-        *(u32x4*)(lds + row * LDK + col) = val;
+    for (int i = 0; i < PER_WAVE; ++i) {
+        const int ld = wave * PER_WAVE + i;                 // wave-uniform
+        const int row = ld * G::ROWS_PER_LOAD + lane / G::CPR;
+        const int phys = lane % G::CPR;
+        const int logical = phys ^ (IS_V ? G::swz_v(row) : G::swz_k(row));
+        int grow = key0 + row;
+        grow = grow < kv_len ? grow : kv_len - 1;
+        const __bf16* g = src + (size_t)grow * D + logical * 8;
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)g,
+                                         (__attribute__((address_space(3))) void*)(lds + ld * 1024), 16, 0, 0);
+    }
+}
+
+struct SoftmaxState {
+    float m;      // max used for the exponent (raw score units); same in both lane halves
+    float l;      // this lane's partial sum of probabilities
+};
+
+// One 64-key tile: S^T = K Q^T, online softmax, O^T += V^T P^T.
+template <int D>
+__device__ __forceinline__ void compute_tile(const char* lds_k, const char* lds_v, const bf16x8 (&qf)[D / 16],
+                                             f32x16 (&acc)[D / 32], SoftmaxState& st_, int key0, int kv_len,
+                                             float c, float tau, int n, int h, int tr_row, int tr_col)
+{
+    typedef Geo<D> G;
+    constexpr int KS = D / 16;
+    constexpr int DB = D / 32;
+
+    // ---- S^T = K Q^T : two 32-key row blocks
+    f32x16 st[2];
+    const int kx = h ^ G::swz_k(n);                        // chunk (2t+h) ^ swz == (2t) ^ kx
+#pragma unroll
+    for (int rb = 0; rb < 2; ++rb) {
+#pragma unroll
+        for (int j = 0; j < 16; ++j) st[rb][j] = 0.f;
+#pragma unroll
+        for (int t = 0; t < KS; ++t) {
+            const bf16x8 a = *(const bf16x8*)(lds_k + (rb * 32 + n) * G::ROW_BYTES + (((2 * t) ^ kx) << 4));
+            st[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[t], st[rb], 0, 0, 0);
+        }
+    }
+    // register i of row block rb holds key  key0 + 32 rb + 8 (i/4) + 4 h + i%4
+    if (key0 + KT > kv_len) {
+#pragma unroll
+        for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const int key = key0 + 32 * rb + 8 * (i >> 2) + 4 * h + (i & 3);
+                if (key >= kv_len) st[rb][i] = -INFINITY;
+            }
+    }
+
+    // ---- online softmax (one query per lane; the two lane halves hold disjoint keys)
+    float mx = fmaxf(st[0][0], st[1][0]);
+#pragma unroll
+    for (int i = 1; i < 16; ++i) mx = fmaxf(fmaxf(mx, st[0][i]), st[1][i]);
+    {
+        auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(mx), __float_as_uint(mx), false, false);
+        mx = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
+    }
+    // Lazy rescale: keep the old reference max while the new one exceeds it by at most
+    // tau (probabilities then stay below 2^8); any reference gives the same quotient.
+    if (__builtin_amdgcn_ballot_w64(mx > st_.m + tau) != 0ull) {
+        const float m_new = fmaxf(st_.m, mx);              // finite: every visited tile has a valid key
+        const float alpha = __builtin_amdgcn_exp2f((st_.m - m_new) * c);
+        st_.m = m_new;
+        st_.l *= alpha;
+#pragma unroll
+        for (int i = 0; i < DB; ++i)
+#pragma unroll
+            for (int j = 0; j < 16; ++j) acc[i][j] *= alpha;
+    }
+    const float mc = st_.m * c;
+    float rs0 = 0.f, rs1 = 0.f;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        const float e0 = __builtin_amdgcn_exp2f(__builtin_fmaf(st[0][i], c, -mc));
+        const float e1 = __builtin_amdgcn_exp2f(__builtin_fmaf(st[1][i], c, -mc));
+        st[0][i] = e0; st[1][i] = e1;
+        rs0 += e0; rs1 += e1;
+    }
+    st_.l += rs0 + rs1;
+
+    // ---- O^T += V^T P^T
+    const int vx = G::swz_v(tr_row) >> 2;                  // 64-byte group swizzle of this lane's rows
+#pragma unroll
+    for (int rb = 0; rb < 2; ++rb) {
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+            bf16x8 pb;                                      // keys 16t + {4h..4h+3, 8+4h..8+4h+3} of row block rb
+#pragma unroll
+            for (int i = 0; i < 8; ++i) pb[i] = (__bf16)st[rb][8 * t + i];
+            const char* vrow = lds_v + (rb * 32 + 16 * t + 4 * h + tr_row) * G::ROW_BYTES + tr_col * 2;
+#pragma unroll
+            for (int db = 0; db < DB; ++db) {
+                const int goff = (db ^ vx) << 6;
+                const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, vrow + goff));
+                const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, vrow + 8 * G::ROW_BYTES + goff));
+                const s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+                acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                    __builtin_bit_cast(bf16x8, both), pb, acc[db], 0, 0, 0);
+            }
+        }
     }
 }
 
 template <int D, int NW>
-__global__ __launch_bounds__(64 * NW) void attn_kernel(const AttnParams p)
+__global__ __launch_bounds__(64 * NW, 2) void attn_kernel(const AttnParams p)
 {
-    constexpr int NT = 64 * NW;
+    typedef Geo<D> G;
     constexpr int QT = 32 * NW;
-    constexpr int LDK = Tile<D>::LDK;
     constexpr int KS = D / 16;                    // k-steps of the QK^T product
     constexpr int DB = D / 32;                    // 32-row blocks of O^T
 
-    __shared__ __attribute__((aligned(16))) __bf16 lds_k[KT * LDK];
-    __shared__ __attribute__((aligned(16))) __bf16 lds_v[KT * LDK];
+    // double-buffered K and V tiles; separate arrays so the compiler can tell the buffer
+    // being filled from the buffer being read
+    __shared__ __attribute__((aligned(1024))) char lds_k0[G::TILE_BYTES];
+    __shared__ __attribute__((aligned(1024))) char lds_k1[G::TILE_BYTES];
+    __shared__ __attribute__((aligned(1024))) char lds_v0[G::TILE_BYTES];
+    __shared__ __attribute__((aligned(1024))) char lds_v1[G::TILE_BYTES];
 
     // XCD-aware work mapping: the dispatcher deals consecutive workgroup ids
     // round-robin over the 8 XCDs, so give each XCD a contiguous run of items
@@ -127,13 +244,13 @@ __global__ __launch_bounds__(64 * NW) void attn_kernel(const AttnParams p)
     const int wg = blockIdx.x;
     int item = (wg % XCDS) * p.chunk + wg / XCDS;
     if (item >= p.items) return;
-    if (p.order) item = p.order[item];
+    if (p.order) item = ((const __attribute__((address_space(4))) int32_t*)p.order)[item];
     const int bh = item / p.nq;
     const int qi = item % p.nq;
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
-    const int wave = tid >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int n = lane & 31;                      // query within the wave / MFMA column
     const int h = lane >> 5;                      // lane half
     const int kv_len = p.kv_len;
@@ -143,6 +260,34 @@ __global__ __launch_bounds__(64 * NW) void attn_kernel(const AttnParams p)
     const __bf16* __restrict__ K = p.k + base;
     const __bf16* __restrict__ V = p.v + base;
     __bf16* __restrict__ O = p.o + base;
+
+    // key tiles to visit: tile t -> first key
+    // (the kept-tile list is read through the constant address space so that the reads
+    // are scalar loads: they must not share a counter with the tile copies in flight)
+    typedef const __attribute__((address_space(4))) int32_t* cptr_t;
+    const int ss = p.sub_shift;                   // log2(64-key tiles per mask block)
+    const bool sparse = p.counts != nullptr;
+    cptr_t list = (cptr_t)(p.index + (size_t)item * p.nb);
+    int T;
+    if (sparse) {
+        const int n_blocks = ((cptr_t)p.counts)[item];
+        T = n_blocks << ss;
+        if (n_blocks > 0 && (((list[n_blocks - 1] + 1) << ss) - 1) * KT >= kv_len) T -= 1;
+    } else {
+        T = (kv_len + KT - 1) / KT;
+    }
+    auto tile_key0 = [&](int t) -> int {
+        if (!sparse) return t * KT;
+        return ((list[t >> ss] << ss) + (t & ((1 << ss) - 1))) * KT;
+    };
+
+    int key_cur = 0, key_nxt = 0;
+    if (T > 0) {
+        key_cur = tile_key0(0);
+        issue_tile<D, NW, false>(K, key_cur, kv_len, lds_k0, wave, lane);
+        issue_tile<D, NW, true>(V, key_cur, kv_len, lds_v0, wave, lane);
+        if (T > 1) key_nxt = tile_key0(1);
+    }
 
     const int qrow = qi * QT + wave * 32 + n;     // this lane's query row
     const bool qvalid = qrow < kv_len;            // kv_len <= N
@@ -161,105 +306,45 @@ __global__ __launch_bounds__(64 * NW) void attn_kernel(const AttnParams p)
     for (int i = 0; i < DB; ++i)
 #pragma unroll
         for (int j = 0; j < 16; ++j) acc[i][j] = 0.f;
-    float m_run = -INFINITY;                      // running max of raw scores (shared by both halves)
-    float l_run = 0.f;                            // this lane's partial running sum
-
-    // key tiles to visit
-    const int sub = p.counts ? p.block / KT : 1;  // 64-key tiles per mask block
-    const int n_blocks = p.counts ? p.counts[item] : (kv_len + KT - 1) / KT;
-    const int32_t* list = p.counts ? p.index + (size_t)item * p.nb : nullptr;
+    SoftmaxState sm;
+    sm.m = -INFINITY;
+    sm.l = 0.f;
+    const float tau = 8.0f / p.c;                 // 2^8 head-room on the probabilities
 
     // per-lane offsets of the transpose read: within a 16-lane group, lane j points
     // at row j/4, columns 4*(j%4)..+3 of a 4 x 16 patch; lane i receives column i.
     const int tr_row = (lane & 15) >> 2;
     const int tr_col = ((lane & 3) << 2) + (((lane >> 4) & 1) << 4);
 
-    for (int bi = 0; bi < n_blocks; ++bi) {
-        const int blk = list ? list[bi] : bi;
-        for (int s = 0; s < sub; ++s) {
-            const int key0 = (blk * sub + s) * KT;
-            if (key0 >= kv_len) break;            // uniform over the workgroup
-
-            __syncthreads();                      // everyone is done reading the previous tile
-            stage_tile<D, NT>(K, key0, kv_len, lds_k, tid);
-            stage_tile<D, NT>(V, key0, kv_len, lds_v, tid);
-            __syncthreads();
-
-            // ---- S^T = K Q^T : two 32-key row blocks
-            f32x16 st[2];
-#pragma unroll
-            for (int rb = 0; rb < 2; ++rb) {
-#pragma unroll
-                for (int j = 0; j < 16; ++j) st[rb][j] = 0.f;
-#pragma unroll
-                for (int t = 0; t < KS; ++t) {
-                    const bf16x8 a = *(const bf16x8*)(lds_k + (rb * 32 + n) * LDK + 16 * t + 8 * h);
-                    st[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[t], st[rb], 0, 0, 0);
-                }
-            }
-            // register i of row block rb holds key  key0 + 32 rb + 8 (i/4) + 4 h + i%4
-            if (key0 + KT > kv_len) {
-#pragma unroll
-                for (int rb = 0; rb < 2; ++rb)
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) {
-                        const int key = key0 + 32 * rb + 8 * (i >> 2) + 4 * h + (i & 3);
-                        if (key >= kv_len) st[rb][i] = -INFINITY;
-                    }
-            }
-
-            // ---- online softmax (one query per lane; halves hold disjoint keys)
-            float mx = st[0][0];
-#pragma unroll
-            for (int rb = 0; rb < 2; ++rb)
-#pragma unroll
-                for (int i = 0; i < 16; ++i) mx = fmaxf(mx, st[rb][i]);
-            {
-                auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(mx), __float_as_uint(mx), false, false);
-                mx = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
-            }
-            const float m_new = fmaxf(m_run, mx);     // finite: every visited tile has a valid key
-            const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * p.c);
-            const float mc = m_new * p.c;
-            m_run = m_new;
-            float rs = 0.f;
-#pragma unroll
-            for (int rb = 0; rb < 2; ++rb)
-#pragma unroll
-                for (int i = 0; i < 16; ++i) {
-                    const float e = __builtin_amdgcn_exp2f(__builtin_fmaf(st[rb][i], p.c, -mc));
-                    st[rb][i] = e;
-                    rs += e;
-                }
-            l_run = l_run * alpha + rs;
-#pragma unroll
-            for (int i = 0; i < DB; ++i)
-#pragma unroll
-                for (int j = 0; j < 16; ++j) acc[i][j] *= alpha;
-
-            // ---- O^T += V^T P^T
-#pragma unroll
-            for (int rb = 0; rb < 2; ++rb) {
-#pragma unroll
-                for (int t = 0; t < 2; ++t) {
-                    bf16x8 pb;                        // keys 16t + {4h..4h+3, 8+4h..8+4h+3} of row block rb
-#pragma unroll
-                    for (int i = 0; i < 8; ++i) pb[i] = (__bf16)st[rb][8 * t + i];
-                    const __bf16* vrow = lds_v + (rb * 32 + 16 * t + 4 * h + tr_row) * LDK + tr_col;
-#pragma unroll
-                    for (int db = 0; db < DB; ++db) {
-                        const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, vrow + db * 32));
-                        const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, vrow + 8 * LDK + db * 32));
-                        const s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-                        acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                            __builtin_bit_cast(bf16x8, both), pb, acc[db], 0, 0, 0);
-                    }
-                }
-            }
+    // Pipeline: tile t is computed out of one buffer pair while the copy of tile t+1 into
+    // the other pair is in flight.  One barrier per tile: after it, tile t is visible to
+    // all wavefronts and all of them have finished reading the buffers of tile t-1.
+    for (int t = 0; t < T; t += 2) {
+        __builtin_amdgcn_s_waitcnt(0x0F70);       // vmcnt(0): my part of tile t has landed
+        __syncthreads();
+        int key_nn = 0;
+        if (t + 1 < T) {
+            issue_tile<D, NW, false>(K, key_nxt, kv_len, lds_k1, wave, lane);
+            issue_tile<D, NW, true>(V, key_nxt, kv_len, lds_v1, wave, lane);
+            if (t + 2 < T) key_nn = tile_key0(t + 2);
         }
+        compute_tile<D>(lds_k0, lds_v0, qf, acc, sm, key_cur, kv_len, p.c, tau, n, h, tr_row, tr_col);
+        if (t + 1 >= T) break;
+
+        __builtin_amdgcn_s_waitcnt(0x0F70);
+        __syncthreads();
+        key_cur = key_nn;
+        if (t + 2 < T) {
+            issue_tile<D, NW, false>(K, key_cur, kv_len, lds_k0, wave, lane);
+            issue_tile<D, NW, true>(V, key_cur, kv_len, lds_v0, wave, lane);
+        }
+        const int key_odd = key_nxt;
+        if (t + 3 < T) key_nxt = tile_key0(t + 3);
+        compute_tile<D>(lds_k1, lds_v1, qf, acc, sm, key_odd, kv_len, p.c, tau, n, h, tr_row, tr_col);
     }
 
     // ---- epilogue: O = acc / l ; register 4j+r of block db holds d = 32 db + 8 j + 4 h + r
+    float l_run = sm.l;
     {
         auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(l_run), __float_as_uint(l_run), false, false);
         l_run = __uint_as_float(sw[0]) + __uint_as_float(sw[1]);
@@ -345,7 +430,7 @@ int rapid_attn_dense(const void* q, const void* k, const void* v, void* o,
     if (items > 0x7fffffffLL / 2) return RAPID_ERR_SHAPE;
     p.items = (int)items;
     p.chunk = (p.items + XCDS - 1) / XCDS;
-    p.block = 0; p.nb = 0;
+    p.block = 0; p.nb = 0; p.sub_shift = 0;
     p.c = scale * LOG2E;
     hipStream_t s = (hipStream_t)stream;
     return D == 64 ? launch_attn<64, 4>(p, s) : launch_attn<128, 4>(p, s);
@@ -386,7 +471,7 @@ int rapid_attn_block_sparse(const void* q, const void* k, const void* v, void* o
     p.nq = nb;
     p.items = (int)rows;
     p.chunk = (p.items + XCDS - 1) / XCDS;
-    p.block = block; p.nb = nb;
+    p.block = block; p.nb = nb; p.sub_shift = block == 128 ? 1 : 0;
     p.c = scale * LOG2E;
     if (block == 128)
         return D == 64 ? launch_attn<64, 4>(p, s) : launch_attn<128, 4>(p, s);
