@@ -34,9 +34,16 @@ typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef short s16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 
 constexpr int KT = 64;          // keys per LDS tile
 constexpr int XCDS = 8;         // L2 domains the dispatcher deals workgroups over
+#ifndef DENSE_QT
+#define DENSE_QT 256            // query rows per workgroup on the dense path
+#endif
+#ifndef DENSE_NS
+#define DENSE_NS 3              // LDS stages on the dense path
+#endif
 constexpr float LOG2E = 1.44269504088896340736f;
 
 #define LDS_PTR(T, p) ((__attribute__((address_space(3))) T*)(p))
@@ -125,8 +132,12 @@ __device__ __forceinline__ void issue_tile(const __bf16* __restrict__ src, int k
         int grow = key0 + row;
         grow = grow < kv_len ? grow : kv_len - 1;
         const __bf16* g = src + (size_t)grow * D + logical * 8;
-        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)g,
-                                         (__attribute__((address_space(3))) void*)(lds + ld * 1024), 16, 0, 0);
+        // global_load_lds_dwordx4: LDS address = M0 + 16 * lane.  Written as assembly so that
+        // the copy pipeline is ordered only by the explicit vmcnt waits and barriers of the
+        // main loop (the compiler would otherwise wait for all copies before LDS reads it
+        // cannot disambiguate).  M0 has no other user in this kernel.
+        const unsigned dst = (unsigned)(size_t)LDS_PTR(char, lds + ld * 1024);
+        asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(dst), "v"(g));
     }
 }
 
@@ -134,6 +145,74 @@ struct SoftmaxState {
     float m;      // max used for the exponent (raw score units); same in both lane halves
     float l;      // this lane's partial sum of probabilities
 };
+
+// ---------------------------------------------------------------------------
+// V^T fragments through the LDS transpose read.  These reads are written as inline
+// assembly with their own s_waitcnt: issued through the compiler builtin they carry no
+// alias scope, and the compiler then makes every one of them wait for ALL outstanding
+// global->LDS copies (vmcnt(0)), which would serialise the copy pipeline.  LDS returns
+// data in order, so "lgkmcnt(N)" = everything but the newest N LDS requests has arrived.
+// ---------------------------------------------------------------------------
+template <int D>
+struct VFrag {
+    u32x2 lo[D / 32];      // keys 4h+r      of the 16-key step, for each 32-row block of O^T
+    u32x2 hi[D / 32];      // keys 8+4h+r
+};
+
+// Request the fragments of the 16 keys starting at tile row ROW0 (a multiple of 16).
+// vaddr[db] = LDS byte address of this lane's patch in tile row 0 for O^T block db.
+template <int D, int ROW0>
+__device__ __forceinline__ void vt_request(VFrag<D>& f, const unsigned (&vaddr)[D / 32])
+{
+    constexpr int RB = Geo<D>::ROW_BYTES;
+#pragma unroll
+    for (int db = 0; db < D / 32; ++db) {
+        asm volatile("ds_read_b64_tr_b16 %0, %2 offset:%3\n\tds_read_b64_tr_b16 %1, %2 offset:%4"
+                     : "=&v"(f.lo[db]), "=&v"(f.hi[db])
+                     : "v"(vaddr[db]), "i"(ROW0 * RB), "i"((ROW0 + 8) * RB));
+    }
+}
+
+// Wait until the fragments in `f` have arrived; MORE = one newer request group is in flight
+// and may stay in flight.  The fragments are in/out operands so that their uses are ordered
+// after the wait.
+template <int D, bool MORE>
+__device__ __forceinline__ void vt_wait(VFrag<D>& f)
+{
+    constexpr int N = MORE ? 2 * (D / 32) : 0;
+    if constexpr (D == 128) {
+        asm volatile("s_waitcnt lgkmcnt(%8)"
+                     : "+v"(f.lo[0]), "+v"(f.hi[0]), "+v"(f.lo[1]), "+v"(f.hi[1]),
+                       "+v"(f.lo[2]), "+v"(f.hi[2]), "+v"(f.lo[3]), "+v"(f.hi[3])
+                     : "i"(N));
+    } else {
+        asm volatile("s_waitcnt lgkmcnt(%4)"
+                     : "+v"(f.lo[0]), "+v"(f.hi[0]), "+v"(f.lo[1]), "+v"(f.hi[1])
+                     : "i"(N));
+    }
+}
+
+// Products of one 16-key group G = 2 rb + t; requests the fragments of group G+1 first.
+template <int D, int GRP>
+__device__ __forceinline__ void pv_group(VFrag<D> (&vfrag)[2], const unsigned (&vaddr)[D / 32],
+                                         const f32x16 (&st)[2], f32x16 (&acc)[D / 32])
+{
+    constexpr int rb = GRP >> 1, t = GRP & 1;
+    if constexpr (GRP < 3) {
+        vt_request<D, ((GRP + 1) >> 1) * 32 + ((GRP + 1) & 1) * 16>(vfrag[(GRP + 1) & 1], vaddr);
+        vt_wait<D, true>(vfrag[GRP & 1]);
+    } else {
+        vt_wait<D, false>(vfrag[GRP & 1]);
+    }
+    bf16x8 pb;                                              // keys 16t + {4h..4h+3, 8+4h..8+4h+3} of row block rb
+#pragma unroll
+    for (int i = 0; i < 8; ++i) pb[i] = (__bf16)st[rb][8 * t + i];
+#pragma unroll
+    for (int db = 0; db < D / 32; ++db) {
+        const u32x4 both = __builtin_shufflevector(vfrag[GRP & 1].lo[db], vfrag[GRP & 1].hi[db], 0, 1, 2, 3);
+        acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, both), pb, acc[db], 0, 0, 0);
+    }
+}
 
 // One 64-key tile: S^T = K Q^T, online softmax, O^T += V^T P^T.
 template <int D>
@@ -169,6 +248,17 @@ __device__ __forceinline__ void compute_tile(const char* lds_k, const char* lds_
             }
     }
 
+    // V^T fragments of the first 16 keys: requested now, consumed after the softmax
+    unsigned vaddr[DB];
+    {
+        const unsigned vbase = (unsigned)(size_t)LDS_PTR(const char, lds_v) + (4 * h + tr_row) * G::ROW_BYTES + tr_col * 2;
+        const int vx = G::swz_v(tr_row) >> 2;              // 64-byte group swizzle of this lane's rows
+#pragma unroll
+        for (int db = 0; db < DB; ++db) vaddr[db] = vbase + ((db ^ vx) << 6);
+    }
+    VFrag<D> vfrag[2];
+    vt_request<D, 0>(vfrag[0], vaddr);
+
     // ---- online softmax (one query per lane; the two lane halves hold disjoint keys)
     float mx = fmaxf(st[0][0], st[1][0]);
 #pragma unroll
@@ -200,43 +290,49 @@ __device__ __forceinline__ void compute_tile(const char* lds_k, const char* lds_
     }
     st_.l += rs0 + rs1;
 
-    // ---- O^T += V^T P^T
-    const int vx = G::swz_v(tr_row) >> 2;                  // 64-byte group swizzle of this lane's rows
-#pragma unroll
-    for (int rb = 0; rb < 2; ++rb) {
-#pragma unroll
-        for (int t = 0; t < 2; ++t) {
-            bf16x8 pb;                                      // keys 16t + {4h..4h+3, 8+4h..8+4h+3} of row block rb
-#pragma unroll
-            for (int i = 0; i < 8; ++i) pb[i] = (__bf16)st[rb][8 * t + i];
-            const char* vrow = lds_v + (rb * 32 + 16 * t + 4 * h + tr_row) * G::ROW_BYTES + tr_col * 2;
-#pragma unroll
-            for (int db = 0; db < DB; ++db) {
-                const int goff = (db ^ vx) << 6;
-                const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, vrow + goff));
-                const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, vrow + 8 * G::ROW_BYTES + goff));
-                const s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-                acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                    __builtin_bit_cast(bf16x8, both), pb, acc[db], 0, 0, 0);
-            }
-        }
-    }
+    // ---- O^T += V^T P^T.  Four groups (rb, t) of 16 keys; the V^T fragments of group g+1
+    // are requested before the products of group g are issued (group 0 was requested
+    // before the softmax).
+    pv_group<D, 0>(vfrag, vaddr, st, acc);
+    pv_group<D, 1>(vfrag, vaddr, st, acc);
+    pv_group<D, 2>(vfrag, vaddr, st, acc);
+    pv_group<D, 3>(vfrag, vaddr, st, acc);
 }
 
-template <int D, int NW>
-__global__ __launch_bounds__(64 * NW, 2) void attn_kernel(const AttnParams p)
+// s_waitcnt with only the vector-memory counter constrained (gfx9 encoding: vmcnt in
+// bits 3:0 and 15:14, expcnt 6:4 and lgkmcnt 11:8 left at their maxima)
+template <int VM>
+__device__ __forceinline__ void wait_vmcnt()
+{
+    static_assert(VM >= 0 && VM < 64, "vmcnt is a 6-bit counter");
+    __builtin_amdgcn_s_waitcnt(0x0F70 | (VM & 15) | ((VM >> 4) << 14));
+}
+
+// NW wavefronts x 32 queries; NS LDS stages (tile t lives in stage t % NS, its copy is
+// issued NS-1 tiles ahead); WPE = wavefronts per SIMD the register budget is held to.
+template <int D, int NW, int NS, int WPE>
+__global__ __launch_bounds__(64 * NW, WPE) void attn_kernel(const AttnParams p)
 {
     typedef Geo<D> G;
     constexpr int QT = 32 * NW;
     constexpr int KS = D / 16;                    // k-steps of the QK^T product
     constexpr int DB = D / 32;                    // 32-row blocks of O^T
+    constexpr int LPT = 2 * G::LOADS / NW;        // copy instructions per wavefront per tile (K + V)
 
-    // double-buffered K and V tiles; separate arrays so the compiler can tell the buffer
-    // being filled from the buffer being read
+    // K and V tile rings.  Every stage is its own array (unused ones are dropped) and is
+    // selected with compile-time constants only: the compiler then knows that the stage
+    // being filled is not the stage being read and adds no wait between the two.
+    static_assert(NS >= 2 && NS <= 4, "2 to 4 stages");
     __shared__ __attribute__((aligned(1024))) char lds_k0[G::TILE_BYTES];
     __shared__ __attribute__((aligned(1024))) char lds_k1[G::TILE_BYTES];
+    __shared__ __attribute__((aligned(1024))) char lds_k2[G::TILE_BYTES];
+    __shared__ __attribute__((aligned(1024))) char lds_k3[G::TILE_BYTES];
     __shared__ __attribute__((aligned(1024))) char lds_v0[G::TILE_BYTES];
     __shared__ __attribute__((aligned(1024))) char lds_v1[G::TILE_BYTES];
+    __shared__ __attribute__((aligned(1024))) char lds_v2[G::TILE_BYTES];
+    __shared__ __attribute__((aligned(1024))) char lds_v3[G::TILE_BYTES];
+    auto stage_k = [&](int st) -> char* { return st == 0 ? lds_k0 : st == 1 ? lds_k1 : st == 2 ? lds_k2 : lds_k3; };
+    auto stage_v = [&](int st) -> char* { return st == 0 ? lds_v0 : st == 1 ? lds_v1 : st == 2 ? lds_v2 : lds_v3; };
 
     // XCD-aware work mapping: the dispatcher deals consecutive workgroup ids
     // round-robin over the 8 XCDs, so give each XCD a contiguous run of items
@@ -281,13 +377,19 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_kernel(const AttnParams p)
         return ((list[t >> ss] << ss) + (t & ((1 << ss) - 1))) * KT;
     };
 
-    int key_cur = 0, key_nxt = 0;
-    if (T > 0) {
-        key_cur = tile_key0(0);
-        issue_tile<D, NW, false>(K, key_cur, kv_len, lds_k0, wave, lane);
-        issue_tile<D, NW, true>(V, key_cur, kv_len, lds_v0, wave, lane);
-        if (T > 1) key_nxt = tile_key0(1);
+    // prologue: copies of the first NS-1 tiles; key_ring[s] = first key of the tile in stage s
+    int key_ring[NS];
+#pragma unroll
+    for (int st = 0; st < NS; ++st) key_ring[st] = 0;
+#pragma unroll
+    for (int st = 0; st < NS - 1; ++st) {
+        if (st < T) {
+            key_ring[st] = tile_key0(st);
+            issue_tile<D, NW, false>(K, key_ring[st], kv_len, stage_k(st), wave, lane);
+            issue_tile<D, NW, true>(V, key_ring[st], kv_len, stage_v(st), wave, lane);
+        }
     }
+    int key_pref = (NS - 1 < T) ? tile_key0(NS - 1) : 0;   // first key of the next tile to issue
 
     const int qrow = qi * QT + wave * 32 + n;     // this lane's query row
     const bool qvalid = qrow < kv_len;            // kv_len <= N
@@ -316,31 +418,35 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_kernel(const AttnParams p)
     const int tr_row = (lane & 15) >> 2;
     const int tr_col = ((lane & 3) << 2) + (((lane >> 4) & 1) << 4);
 
-    // Pipeline: tile t is computed out of one buffer pair while the copy of tile t+1 into
-    // the other pair is in flight.  One barrier per tile: after it, tile t is visible to
-    // all wavefronts and all of them have finished reading the buffers of tile t-1.
-    for (int t = 0; t < T; t += 2) {
-        __builtin_amdgcn_s_waitcnt(0x0F70);       // vmcnt(0): my part of tile t has landed
-        __syncthreads();
-        int key_nn = 0;
-        if (t + 1 < T) {
-            issue_tile<D, NW, false>(K, key_nxt, kv_len, lds_k1, wave, lane);
-            issue_tile<D, NW, true>(V, key_nxt, kv_len, lds_v1, wave, lane);
-            if (t + 2 < T) key_nn = tile_key0(t + 2);
-        }
-        compute_tile<D>(lds_k0, lds_v0, qf, acc, sm, key_cur, kv_len, p.c, tau, n, h, tr_row, tr_col);
-        if (t + 1 >= T) break;
+    // The Q fragments must have arrived before the loop: a wait for them inside the loop
+    // would also wait for every tile copy in flight.
+    wait_vmcnt<0>();
 
-        __builtin_amdgcn_s_waitcnt(0x0F70);
-        __syncthreads();
-        key_cur = key_nn;
-        if (t + 2 < T) {
-            issue_tile<D, NW, false>(K, key_cur, kv_len, lds_k0, wave, lane);
-            issue_tile<D, NW, true>(V, key_cur, kv_len, lds_v0, wave, lane);
+    // Pipeline: tile t is computed out of stage t % NS while the copies of tiles
+    // t+1 .. t+NS-1 are in flight.  One barrier per tile: after it, tile t is visible to
+    // all wavefronts and all of them have finished reading the stage of tile t-1, which
+    // is the stage the copy of tile t+NS-1 is then issued into.
+    for (int t0 = 0; t0 < T; t0 += NS) {
+#pragma unroll
+        for (int st = 0; st < NS; ++st) {
+            const int t = t0 + st;
+            if (t >= T) break;
+            // my copies of tile t have landed once at most the copies of the tiles issued
+            // after it are outstanding (vector-memory operations complete in order)
+            if (NS >= 3 && t + NS - 2 < T) wait_vmcnt<(NS - 2) * LPT>();
+            else if (NS >= 4 && t + NS - 3 < T) wait_vmcnt<(NS >= 4 ? (NS - 3) * LPT : 0)>();
+            else if (NS >= 4 && t + 1 < T) wait_vmcnt<(NS >= 4 ? LPT : 0)>();
+            else wait_vmcnt<0>();
+            __syncthreads();
+            const int nst = (st + NS - 1) % NS;    // a constant once unrolled
+            if (t + NS - 1 < T) {
+                key_ring[nst] = key_pref;
+                issue_tile<D, NW, false>(K, key_pref, kv_len, stage_k(nst), wave, lane);
+                issue_tile<D, NW, true>(V, key_pref, kv_len, stage_v(nst), wave, lane);
+                if (t + NS < T) key_pref = tile_key0(t + NS);
+            }
+            compute_tile<D>(stage_k(st), stage_v(st), qf, acc, sm, key_ring[st], kv_len, p.c, tau, n, h, tr_row, tr_col);
         }
-        const int key_odd = key_nxt;
-        if (t + 3 < T) key_nxt = tile_key0(t + 3);
-        compute_tile<D>(lds_k1, lds_v1, qf, acc, sm, key_odd, kv_len, p.c, tau, n, h, tr_row, tr_col);
     }
 
     // ---- epilogue: O = acc / l ; register 4j+r of block db holds d = 32 db + 8 j + 4 h + r
@@ -400,11 +506,11 @@ int check_common(const void* q, const void* k, const void* v, const void* o,
     return RAPID_OK;
 }
 
-template <int D, int NW>
+template <int D, int NW, int NS, int WPE>
 int launch_attn(const AttnParams& p, hipStream_t stream)
 {
     const int grid = p.chunk * XCDS;
-    hipLaunchKernelGGL((attn_kernel<D, NW>), dim3(grid), dim3(64 * NW), 0, stream, p);
+    hipLaunchKernelGGL((attn_kernel<D, NW, NS, WPE>), dim3(grid), dim3(64 * NW), 0, stream, p);
     return hipGetLastError() == hipSuccess ? RAPID_OK : RAPID_ERR_DEVICE;
 }
 
@@ -425,7 +531,7 @@ int rapid_attn_dense(const void* q, const void* k, const void* v, void* o,
     p.q = (const __bf16*)q; p.k = (const __bf16*)k; p.v = (const __bf16*)v; p.o = (__bf16*)o;
     p.counts = nullptr; p.order = nullptr; p.index = nullptr;
     p.H = H; p.N = N; p.kv_len = kv_len;
-    p.nq = (N + 127) / 128;
+    p.nq = (N + DENSE_QT - 1) / DENSE_QT;
     const long long items = (long long)B * H * p.nq;
     if (items > 0x7fffffffLL / 2) return RAPID_ERR_SHAPE;
     p.items = (int)items;
@@ -433,7 +539,8 @@ int rapid_attn_dense(const void* q, const void* k, const void* v, void* o,
     p.block = 0; p.nb = 0; p.sub_shift = 0;
     p.c = scale * LOG2E;
     hipStream_t s = (hipStream_t)stream;
-    return D == 64 ? launch_attn<64, 4>(p, s) : launch_attn<128, 4>(p, s);
+    return D == 64 ? launch_attn<64, DENSE_QT / 32, DENSE_NS, 2>(p, s)
+                   : launch_attn<128, DENSE_QT / 32, DENSE_NS, 2>(p, s);
 }
 
 int rapid_attn_block_sparse(const void* q, const void* k, const void* v, void* o,
@@ -474,8 +581,8 @@ int rapid_attn_block_sparse(const void* q, const void* k, const void* v, void* o
     p.block = block; p.nb = nb; p.sub_shift = block == 128 ? 1 : 0;
     p.c = scale * LOG2E;
     if (block == 128)
-        return D == 64 ? launch_attn<64, 4>(p, s) : launch_attn<128, 4>(p, s);
-    return D == 64 ? launch_attn<64, 2>(p, s) : launch_attn<128, 2>(p, s);
+        return D == 64 ? launch_attn<64, 4, 2, 2>(p, s) : launch_attn<128, 4, 2, 2>(p, s);
+    return D == 64 ? launch_attn<64, 2, 2, 2>(p, s) : launch_attn<128, 2, 2, 1>(p, s);
 }
 
 size_t rapid_attn_workspace_bytes(int B, int H, int N, int D, int block)
