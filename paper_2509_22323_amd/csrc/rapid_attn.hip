@@ -44,6 +44,9 @@ constexpr int XCDS = 8;         // L2 domains the dispatcher deals workgroups ov
 #ifndef DENSE_NS
 #define DENSE_NS 3              // LDS stages on the dense path
 #endif
+#ifndef DENSE_PINGPONG
+#define DENSE_PINGPONG 1        // dense path: two wavefront groups held in anti-phase
+#endif
 constexpr float LOG2E = 1.44269504088896340736f;
 
 #define LDS_PTR(T, p) ((__attribute__((address_space(3))) T*)(p))
@@ -173,13 +176,11 @@ __device__ __forceinline__ void vt_request(VFrag<D>& f, const unsigned (&vaddr)[
     }
 }
 
-// Wait until the fragments in `f` have arrived; MORE = one newer request group is in flight
-// and may stay in flight.  The fragments are in/out operands so that their uses are ordered
-// after the wait.
-template <int D, bool MORE>
+// Wait until the fragments in `f` have arrived; N = newer LDS requests that may stay in
+// flight.  The fragments are in/out operands so that their uses are ordered after the wait.
+template <int D, int N>
 __device__ __forceinline__ void vt_wait(VFrag<D>& f)
 {
-    constexpr int N = MORE ? 2 * (D / 32) : 0;
     if constexpr (D == 128) {
         asm volatile("s_waitcnt lgkmcnt(%8)"
                      : "+v"(f.lo[0]), "+v"(f.hi[0]), "+v"(f.lo[1]), "+v"(f.hi[1]),
@@ -193,51 +194,96 @@ __device__ __forceinline__ void vt_wait(VFrag<D>& f)
 }
 
 // Products of one 16-key group G = 2 rb + t; requests the fragments of group G+1 first.
-template <int D, int GRP>
+// NEWER = LDS requests issued after the fragments of this group that may stay in flight.
+template <int D, int GRP, int NEWER = 0>
 __device__ __forceinline__ void pv_group(VFrag<D> (&vfrag)[2], const unsigned (&vaddr)[D / 32],
-                                         const f32x16 (&st)[2], f32x16 (&acc)[D / 32])
+                                         const bf16x8 (&pb)[4], f32x16 (&acc)[D / 32])
 {
-    constexpr int rb = GRP >> 1, t = GRP & 1;
     if constexpr (GRP < 3) {
         vt_request<D, ((GRP + 1) >> 1) * 32 + ((GRP + 1) & 1) * 16>(vfrag[(GRP + 1) & 1], vaddr);
-        vt_wait<D, true>(vfrag[GRP & 1]);
+        vt_wait<D, 2 * (D / 32) + NEWER>(vfrag[GRP & 1]);
     } else {
-        vt_wait<D, false>(vfrag[GRP & 1]);
+        vt_wait<D, NEWER>(vfrag[GRP & 1]);
     }
-    bf16x8 pb;                                              // keys 16t + {4h..4h+3, 8+4h..8+4h+3} of row block rb
-#pragma unroll
-    for (int i = 0; i < 8; ++i) pb[i] = (__bf16)st[rb][8 * t + i];
 #pragma unroll
     for (int db = 0; db < D / 32; ++db) {
         const u32x4 both = __builtin_shufflevector(vfrag[GRP & 1].lo[db], vfrag[GRP & 1].hi[db], 0, 1, 2, 3);
-        acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, both), pb, acc[db], 0, 0, 0);
+        acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, both), pb[GRP], acc[db], 0, 0, 0);
     }
 }
 
-// One 64-key tile: S^T = K Q^T, online softmax, O^T += V^T P^T.
+// K fragments (A operand of S^T = K Q^T), requested in batches of two k-steps x two row
+// blocks = 4 x ds_read_b128, through assembly with explicit waits for the same reason as the
+// V^T fragments: batch b+1 is in flight while the four products of batch b are issued.
+struct KBatch {
+    u32x4 f[4];            // [2 * (t & 1) + rb]
+};
+
+// kaddr[t] = LDS byte address of this lane's 16-byte chunk of k-step t in row n of the tile.
+template <int D, int B>
+__device__ __forceinline__ void k_request(KBatch& kb, const unsigned (&kaddr)[D / 16])
+{
+    constexpr int RB32 = 32 * Geo<D>::ROW_BYTES;           // second 32-key row block
+    asm volatile("ds_read_b128 %0, %4\n\tds_read_b128 %1, %4 offset:%6\n\t"
+                 "ds_read_b128 %2, %5\n\tds_read_b128 %3, %5 offset:%6"
+                 : "=&v"(kb.f[0]), "=&v"(kb.f[1]), "=&v"(kb.f[2]), "=&v"(kb.f[3])
+                 : "v"(kaddr[2 * B]), "v"(kaddr[2 * B + 1]), "i"(RB32));
+}
+
+template <bool MORE>
+__device__ __forceinline__ void k_wait(KBatch& kb)
+{
+    asm volatile("s_waitcnt lgkmcnt(%4)"
+                 : "+v"(kb.f[0]), "+v"(kb.f[1]), "+v"(kb.f[2]), "+v"(kb.f[3])
+                 : "i"(MORE ? 4 : 0));
+}
+
+template <int D, int B>
+__device__ __forceinline__ void qk_batch(KBatch (&kb)[2], const unsigned (&kaddr)[D / 16],
+                                         const bf16x8 (&qf)[D / 16], f32x16 (&st)[2])
+{
+    constexpr int NB = D / 32;                             // batches per tile
+    if constexpr (B + 1 < NB) {
+        k_request<D, B + 1>(kb[(B + 1) & 1], kaddr);
+        k_wait<true>(kb[B & 1]);
+    } else {
+        k_wait<false>(kb[B & 1]);
+    }
+#pragma unroll
+    for (int tt = 0; tt < 2; ++tt)
+#pragma unroll
+        for (int rb = 0; rb < 2; ++rb)
+            st[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kb[B & 1].f[2 * tt + rb]),
+                                                             qf[2 * B + tt], st[rb], 0, 0, 0);
+}
+
 template <int D>
-__device__ __forceinline__ void compute_tile(const char* lds_k, const char* lds_v, const bf16x8 (&qf)[D / 16],
-                                             f32x16 (&acc)[D / 32], SoftmaxState& st_, int key0, int kv_len,
-                                             float c, float tau, int n, int h, int tr_row, int tr_col)
+__device__ __forceinline__ void k_addresses(const char* lds_k, int n, int h, unsigned (&kaddr)[D / 16])
 {
     typedef Geo<D> G;
-    constexpr int KS = D / 16;
-    constexpr int DB = D / 32;
-
-    // ---- S^T = K Q^T : two 32-key row blocks
-    f32x16 st[2];
+    const unsigned kbase = (unsigned)(size_t)LDS_PTR(const char, lds_k) + n * G::ROW_BYTES;
     const int kx = h ^ G::swz_k(n);                        // chunk (2t+h) ^ swz == (2t) ^ kx
 #pragma unroll
-    for (int rb = 0; rb < 2; ++rb) {
+    for (int t = 0; t < D / 16; ++t) kaddr[t] = kbase + (((2 * t) ^ kx) << 4);
+}
+
+// S^T = K Q^T for one 64-key tile: two 32-key row blocks; keys at or beyond kv_len -> -inf.
+// Register i of row block rb holds key  key0 + 32 rb + 8 (i/4) + 4 h + i%4  of query n.
+// Batch 0 of the K fragments must already have been requested into kb[0].
+template <int D>
+__device__ __forceinline__ void qk_tile(KBatch (&kb)[2], const unsigned (&kaddr)[D / 16], const bf16x8 (&qf)[D / 16],
+                                        f32x16 (&st)[2], int key0, int kv_len, int h)
+{
+#pragma unroll
+    for (int rb = 0; rb < 2; ++rb)
 #pragma unroll
         for (int j = 0; j < 16; ++j) st[rb][j] = 0.f;
-#pragma unroll
-        for (int t = 0; t < KS; ++t) {
-            const bf16x8 a = *(const bf16x8*)(lds_k + (rb * 32 + n) * G::ROW_BYTES + (((2 * t) ^ kx) << 4));
-            st[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[t], st[rb], 0, 0, 0);
-        }
+    qk_batch<D, 0>(kb, kaddr, qf, st);
+    qk_batch<D, 1>(kb, kaddr, qf, st);
+    if constexpr (D == 128) {
+        qk_batch<D, 2>(kb, kaddr, qf, st);
+        qk_batch<D, 3>(kb, kaddr, qf, st);
     }
-    // register i of row block rb holds key  key0 + 32 rb + 8 (i/4) + 4 h + i%4
     if (key0 + KT > kv_len) {
 #pragma unroll
         for (int rb = 0; rb < 2; ++rb)
@@ -247,19 +293,17 @@ __device__ __forceinline__ void compute_tile(const char* lds_k, const char* lds_
                 if (key >= kv_len) st[rb][i] = -INFINITY;
             }
     }
+}
 
-    // V^T fragments of the first 16 keys: requested now, consumed after the softmax
-    unsigned vaddr[DB];
-    {
-        const unsigned vbase = (unsigned)(size_t)LDS_PTR(const char, lds_v) + (4 * h + tr_row) * G::ROW_BYTES + tr_col * 2;
-        const int vx = G::swz_v(tr_row) >> 2;              // 64-byte group swizzle of this lane's rows
-#pragma unroll
-        for (int db = 0; db < DB; ++db) vaddr[db] = vbase + ((db ^ vx) << 6);
-    }
-    VFrag<D> vfrag[2];
-    vt_request<D, 0>(vfrag[0], vaddr);
-
-    // ---- online softmax (one query per lane; the two lane halves hold disjoint keys)
+// Online softmax of one tile (one query per lane; the two lane halves hold disjoint keys).
+// Updates the running reference max / partial sum, rescales the accumulators when the
+// reference moves, and leaves the probabilities as bf16 MFMA operands:
+// pb[2 rb + t] = keys 16t + {4h..4h+3, 8+4h..8+4h+3} of row block rb.
+template <int D>
+__device__ __forceinline__ void softmax_tile(const f32x16 (&st)[2], f32x16 (&acc)[D / 32], SoftmaxState& st_,
+                                             float c, float tau, bf16x8 (&pb)[4])
+{
+    constexpr int DB = D / 32;
     float mx = fmaxf(st[0][0], st[1][0]);
 #pragma unroll
     for (int i = 1; i < 16; ++i) mx = fmaxf(fmaxf(mx, st[0][i]), st[1][i]);
@@ -282,21 +326,101 @@ __device__ __forceinline__ void compute_tile(const char* lds_k, const char* lds_
     const float mc = st_.m * c;
     float rs0 = 0.f, rs1 = 0.f;
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-        const float e0 = __builtin_amdgcn_exp2f(__builtin_fmaf(st[0][i], c, -mc));
-        const float e1 = __builtin_amdgcn_exp2f(__builtin_fmaf(st[1][i], c, -mc));
-        st[0][i] = e0; st[1][i] = e1;
-        rs0 += e0; rs1 += e1;
+    for (int g = 0; g < 4; ++g) {
+        const int rb = g >> 1, t = g & 1;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const float e = __builtin_amdgcn_exp2f(__builtin_fmaf(st[rb][8 * t + i], c, -mc));
+            if (i & 1) rs1 += e; else rs0 += e;
+            pb[g][i] = (__bf16)e;
+        }
     }
     st_.l += rs0 + rs1;
+}
 
-    // ---- O^T += V^T P^T.  Four groups (rb, t) of 16 keys; the V^T fragments of group g+1
-    // are requested before the products of group g are issued (group 0 was requested
-    // before the softmax).
-    pv_group<D, 0>(vfrag, vaddr, st, acc);
-    pv_group<D, 1>(vfrag, vaddr, st, acc);
-    pv_group<D, 2>(vfrag, vaddr, st, acc);
-    pv_group<D, 3>(vfrag, vaddr, st, acc);
+// LDS byte addresses of this lane's transpose-read patches in row 0 of a V tile.
+template <int D>
+__device__ __forceinline__ void v_addresses(const char* lds_v, int h, int tr_row, int tr_col, unsigned (&vaddr)[D / 32])
+{
+    typedef Geo<D> G;
+    const unsigned vbase = (unsigned)(size_t)LDS_PTR(const char, lds_v) + (4 * h + tr_row) * G::ROW_BYTES + tr_col * 2;
+    const int vx = G::swz_v(tr_row) >> 2;                  // 64-byte group swizzle of this lane's rows
+#pragma unroll
+    for (int db = 0; db < D / 32; ++db) vaddr[db] = vbase + ((db ^ vx) << 6);
+}
+
+// O^T += V^T P^T for one tile.  Four groups (rb, t) of 16 keys; the V^T fragments of group
+// g+1 are requested before the products of group g are issued; group 0 must already have
+// been requested into vfrag[0].
+template <int D>
+__device__ __forceinline__ void pv_tile(VFrag<D> (&vfrag)[2], const unsigned (&vaddr)[D / 32],
+                                        const bf16x8 (&pb)[4], f32x16 (&acc)[D / 32])
+{
+    pv_group<D, 0>(vfrag, vaddr, pb, acc);
+    pv_group<D, 1>(vfrag, vaddr, pb, acc);
+    pv_group<D, 2>(vfrag, vaddr, pb, acc);
+    pv_group<D, 3>(vfrag, vaddr, pb, acc);
+}
+
+// One 64-key tile in sequence: S^T = K Q^T, online softmax, O^T += V^T P^T.
+template <int D>
+__device__ __forceinline__ void compute_tile(const char* lds_k, const char* lds_v, const bf16x8 (&qf)[D / 16],
+                                             f32x16 (&acc)[D / 32], SoftmaxState& st_, int key0, int kv_len,
+                                             float c, float tau, int n, int h, int tr_row, int tr_col)
+{
+    unsigned kaddr[D / 16];
+    k_addresses<D>(lds_k, n, h, kaddr);
+    KBatch kb[2];
+    k_request<D, 0>(kb[0], kaddr);
+    f32x16 st[2];
+    qk_tile<D>(kb, kaddr, qf, st, key0, kv_len, h);
+    unsigned vaddr[D / 32];
+    v_addresses<D>(lds_v, h, tr_row, tr_col, vaddr);
+    VFrag<D> vfrag[2];
+    vt_request<D, 0>(vfrag[0], vaddr);                     // consumed after the softmax
+    bf16x8 pb[4];
+    softmax_tile<D>(st, acc, st_, c, tau, pb);
+    pv_tile<D>(vfrag, vaddr, pb, acc);
+}
+
+// Epilogue: O = acc / l as bf16.  Register 4j+r of block db holds d = 32 db + 8 j + 4 h + r
+// of this lane's query; rows at or beyond kv_len and rows without any kept key become 0.
+template <int D>
+__device__ __forceinline__ void write_output(__bf16* __restrict__ O, const f32x16 (&acc)[D / 32], float l_part,
+                                             int qrow, bool qvalid, int N, int h)
+{
+    float l_run = l_part;
+    {
+        auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(l_run), __float_as_uint(l_run), false, false);
+        l_run = __uint_as_float(sw[0]) + __uint_as_float(sw[1]);
+    }
+    const float inv = (qvalid && l_run > 0.f) ? 1.0f / l_run : 0.f;
+    if (qrow < N) {
+#pragma unroll
+        for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                bf16x4 ov;
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const float x = acc[db][4 * j + r] * inv;
+                    ov[r] = (__bf16)((inv != 0.f) ? x : 0.f);
+                }
+                *(bf16x4*)(O + (size_t)qrow * D + 32 * db + 8 * j + 4 * h) = ov;
+            }
+    }
+}
+
+// Q^T fragments (B operand of S^T = K Q^T): lane (n, h) holds Q[qrow][16t + 8h .. +8].
+template <int D>
+__device__ __forceinline__ void load_q(const __bf16* __restrict__ Q, int qrow, bool qvalid, int h, bf16x8 (&qf)[D / 16])
+{
+#pragma unroll
+    for (int t = 0; t < D / 16; ++t) {
+        u32x4 raw = {0u, 0u, 0u, 0u};
+        if (qvalid) raw = *(const u32x4*)(Q + (size_t)qrow * D + 16 * t + 8 * h);
+        qf[t] = __builtin_bit_cast(bf16x8, raw);
+    }
 }
 
 // s_waitcnt with only the vector-memory counter constrained (gfx9 encoding: vmcnt in
@@ -394,14 +518,8 @@ __global__ __launch_bounds__(64 * NW, WPE) void attn_kernel(const AttnParams p)
     const int qrow = qi * QT + wave * 32 + n;     // this lane's query row
     const bool qvalid = qrow < kv_len;            // kv_len <= N
 
-    // Q^T fragments (B operand): lane (n, h) holds Q[qrow][16t + 8h .. +8].
     bf16x8 qf[KS];
-#pragma unroll
-    for (int t = 0; t < KS; ++t) {
-        u32x4 raw = {0u, 0u, 0u, 0u};
-        if (qvalid) raw = *(const u32x4*)(Q + (size_t)qrow * D + 16 * t + 8 * h);
-        qf[t] = __builtin_bit_cast(bf16x8, raw);
-    }
+    load_q<D>(Q, qrow, qvalid, h, qf);
 
     f32x16 acc[DB];
 #pragma unroll
@@ -449,27 +567,169 @@ __global__ __launch_bounds__(64 * NW, WPE) void attn_kernel(const AttnParams p)
         }
     }
 
-    // ---- epilogue: O = acc / l ; register 4j+r of block db holds d = 32 db + 8 j + 4 h + r
-    float l_run = sm.l;
+    write_output<D>(O, acc, sm.l, qrow, qvalid, p.N, h);
+}
+
+// Values computed from registers only carry no ordering against a barrier; an empty volatile
+// assembly statement that "modifies" them makes them complete before whatever follows it.
+__device__ __forceinline__ void pin_in_phase(bf16x8 (&pb)[4], float& l)
+{
+    u32x4 a = __builtin_bit_cast(u32x4, pb[0]), b = __builtin_bit_cast(u32x4, pb[1]);
+    u32x4 c = __builtin_bit_cast(u32x4, pb[2]), d = __builtin_bit_cast(u32x4, pb[3]);
+    asm volatile("" : "+v"(a), "+v"(b), "+v"(c), "+v"(d), "+v"(l));
+    pb[0] = __builtin_bit_cast(bf16x8, a); pb[1] = __builtin_bit_cast(bf16x8, b);
+    pb[2] = __builtin_bit_cast(bf16x8, c); pb[3] = __builtin_bit_cast(bf16x8, d);
+}
+
+// Workgroup barrier that is also a boundary for the instruction scheduler: register-only
+// work (the softmax arithmetic) must not drift from its phase into the neighbouring one.
+__device__ __forceinline__ void phase_barrier()
+{
+    __builtin_amdgcn_sched_barrier(0);
+    __syncthreads();
+    __builtin_amdgcn_sched_barrier(0);
+}
+
+// ---------------------------------------------------------------------------
+// Dense path: 256 queries per workgroup, 8 wavefronts in two groups of four (one wavefront
+// of each group on every SIMD), 4 LDS stages, tile copies issued 3 tiles ahead.
+//
+// Per tile a wavefront alternates two phases separated by workgroup barriers:
+//   B(j)  softmax of S_j                      -- VALU / transcendental work
+//   A(j)  O^T += V_j^T P_j^T ; S_{j+1} = K_{j+1} Q^T   -- 32 MFMAs, LDS reads
+// Group 1 enters the loop one barrier later than group 0, so between any two barriers one
+// group is in a B phase while the other is in an A phase: the two wavefronts that share a
+// SIMD are held in anti-phase and the matrix pipe of one overlaps the vector work of the
+// other, instead of both running the same phase in lock-step after every barrier.
+// Every barrier is executed by all wavefronts (group 0 makes up its missing one at the end).
+// Copy bookkeeping (slot = interval between two barriers; group 0 runs A(j) in slot 2j+2,
+// group 1 in slot 2j+3): tile j+3 is issued at the start of A(j) into the stage of tile j-1,
+// which both groups have finished (group 1's A(j-1) is slot 2j+1); every wavefront waits for
+// its share of tile j+1 before its first barrier of iteration j, i.e. before barrier 2j+2 at
+// the latest, which precedes the first use of tile j+1 (group 0's A(j)).
+// ---------------------------------------------------------------------------
+template <int D>
+__global__ __launch_bounds__(512, 2) void attn_dense_pp_kernel(const AttnParams p)
+{
+    typedef Geo<D> G;
+    constexpr int NW = 8, QT = 256, KS = D / 16, DB = D / 32;
+    constexpr int LPT = 2 * G::LOADS / NW;        // copy instructions per wavefront per tile (K + V)
+
+    __shared__ __attribute__((aligned(1024))) char lds_k0[G::TILE_BYTES];
+    __shared__ __attribute__((aligned(1024))) char lds_k1[G::TILE_BYTES];
+    __shared__ __attribute__((aligned(1024))) char lds_k2[G::TILE_BYTES];
+    __shared__ __attribute__((aligned(1024))) char lds_k3[G::TILE_BYTES];
+    __shared__ __attribute__((aligned(1024))) char lds_v0[G::TILE_BYTES];
+    __shared__ __attribute__((aligned(1024))) char lds_v1[G::TILE_BYTES];
+    __shared__ __attribute__((aligned(1024))) char lds_v2[G::TILE_BYTES];
+    __shared__ __attribute__((aligned(1024))) char lds_v3[G::TILE_BYTES];
+    auto stage_k = [&](int st) -> char* { return st == 0 ? lds_k0 : st == 1 ? lds_k1 : st == 2 ? lds_k2 : lds_k3; };
+    auto stage_v = [&](int st) -> char* { return st == 0 ? lds_v0 : st == 1 ? lds_v1 : st == 2 ? lds_v2 : lds_v3; };
+
+    const int wg = blockIdx.x;
+    const int item = (wg % XCDS) * p.chunk + wg / XCDS;     // XCD-aware: see attn_kernel
+    if (item >= p.items) return;
+    const int bh = item / p.nq;
+    const int qi = item % p.nq;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int group = wave >> 2;
+    const int n = lane & 31;
+    const int h = lane >> 5;
+    const int kv_len = p.kv_len;
+
+    const size_t base = (size_t)bh * p.N * D;
+    const __bf16* __restrict__ Q = p.q + base;
+    const __bf16* __restrict__ K = p.k + base;
+    const __bf16* __restrict__ V = p.v + base;
+    __bf16* __restrict__ O = p.o + base;
+
+    const int T = (kv_len + KT - 1) / KT;         // >= 1
+
+#pragma unroll
+    for (int st = 0; st < 3; ++st) {
+        if (st < T) {
+            issue_tile<D, NW, false>(K, st * KT, kv_len, stage_k(st), wave, lane);
+            issue_tile<D, NW, true>(V, st * KT, kv_len, stage_v(st), wave, lane);
+        }
+    }
+
+    const int qrow = qi * QT + wave * 32 + n;
+    const bool qvalid = qrow < kv_len;
+    bf16x8 qf[KS];
+    load_q<D>(Q, qrow, qvalid, h, qf);
+
+    f32x16 acc[DB];
+#pragma unroll
+    for (int i = 0; i < DB; ++i)
+#pragma unroll
+        for (int j = 0; j < 16; ++j) acc[i][j] = 0.f;
+    SoftmaxState sm;
+    sm.m = -INFINITY;
+    sm.l = 0.f;
+    const float tau = 8.0f / p.c;
+    const int tr_row = (lane & 15) >> 2;
+    const int tr_col = ((lane & 3) << 2) + (((lane >> 4) & 1) << 4);
+
+    wait_vmcnt<0>();                              // Q fragments and the first tiles
+    __syncthreads();
+    if (group == 1) __syncthreads();              // group 1 runs one barrier behind
+
+    f32x16 st[2];
     {
-        auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(l_run), __float_as_uint(l_run), false, false);
-        l_run = __uint_as_float(sw[0]) + __uint_as_float(sw[1]);
+        unsigned kaddr[KS];
+        k_addresses<D>(stage_k(0), n, h, kaddr);
+        KBatch kb[2];
+        k_request<D, 0>(kb[0], kaddr);
+        qk_tile<D>(kb, kaddr, qf, st, 0, kv_len, h);
     }
-    const float inv = (qvalid && l_run > 0.f) ? 1.0f / l_run : 0.f;
-    if (qrow < p.N) {
+
+    for (int j0 = 0; j0 < T; j0 += 4) {
 #pragma unroll
-        for (int db = 0; db < DB; ++db)
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                bf16x4 ov;
-#pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    const float x = acc[db][4 * j + r] * inv;
-                    ov[r] = (__bf16)((inv != 0.f) ? x : 0.f);
-                }
-                *(bf16x4*)(O + (size_t)qrow * D + 32 * db + 8 * j + 4 * h) = ov;
+        for (int s = 0; s < 4; ++s) {
+            const int j = j0 + s;
+            if (j >= T) break;
+            // my share of tile j+1 (outstanding: tiles j+1 and j+2, completing in order)
+            if (j + 2 < T) wait_vmcnt<LPT>();
+            else wait_vmcnt<0>();
+            phase_barrier();
+
+            // ---- B(j)
+            unsigned vaddr[DB];
+            v_addresses<D>(stage_v(s), h, tr_row, tr_col, vaddr);
+            bf16x8 pb[4];
+            softmax_tile<D>(st, acc, sm, p.c, tau, pb);
+            pin_in_phase(pb, sm.l);
+            VFrag<D> vfrag[2];
+            vt_request<D, 0>(vfrag[0], vaddr);
+            phase_barrier();
+
+            // ---- A(j): matrix work first in line at the SIMD's issue arbiter
+            __builtin_amdgcn_s_setprio(3);
+            if (j + 3 < T) {
+                issue_tile<D, NW, false>(K, (j + 3) * KT, kv_len, stage_k((s + 3) & 3), wave, lane);
+                issue_tile<D, NW, true>(V, (j + 3) * KT, kv_len, stage_v((s + 3) & 3), wave, lane);
             }
+            // (the first K fragments of tile j+1 are requested ahead of the last PV products;
+            // for the last tile this re-reads a landed stage and the result is dropped)
+            unsigned kaddr[KS];
+            k_addresses<D>(stage_k((j + 1 < T) ? ((s + 1) & 3) : s), n, h, kaddr);
+            KBatch kb[2];
+            pv_group<D, 0>(vfrag, vaddr, pb, acc);
+            pv_group<D, 1>(vfrag, vaddr, pb, acc);
+            pv_group<D, 2>(vfrag, vaddr, pb, acc);
+            k_request<D, 0>(kb[0], kaddr);
+            pv_group<D, 3, 4>(vfrag, vaddr, pb, acc);
+            if (j + 1 < T) qk_tile<D>(kb, kaddr, qf, st, (j + 1) * KT, kv_len, h);
+            else k_wait<false>(kb[0]);
+            __builtin_amdgcn_s_setprio(0);
+        }
     }
+    if (group == 0) __syncthreads();              // same number of barriers for every wavefront
+
+    write_output<D>(O, acc, sm.l, qrow, qvalid, p.N, h);
 }
 
 // ---------------------------------------------------------------------------
@@ -539,8 +799,17 @@ int rapid_attn_dense(const void* q, const void* k, const void* v, void* o,
     p.block = 0; p.nb = 0; p.sub_shift = 0;
     p.c = scale * LOG2E;
     hipStream_t s = (hipStream_t)stream;
+#if DENSE_PINGPONG
+    {
+        const int grid = p.chunk * XCDS;
+        if (D == 64) hipLaunchKernelGGL((attn_dense_pp_kernel<64>), dim3(grid), dim3(512), 0, s, p);
+        else hipLaunchKernelGGL((attn_dense_pp_kernel<128>), dim3(grid), dim3(512), 0, s, p);
+        return hipGetLastError() == hipSuccess ? RAPID_OK : RAPID_ERR_DEVICE;
+    }
+#else
     return D == 64 ? launch_attn<64, DENSE_QT / 32, DENSE_NS, 2>(p, s)
                    : launch_attn<128, DENSE_QT / 32, DENSE_NS, 2>(p, s);
+#endif
 }
 
 int rapid_attn_block_sparse(const void* q, const void* k, const void* v, void* o,
