@@ -86,7 +86,10 @@ RAPID_API int rapid_attn_dense(const void* q, const void* k, const void* v, void
  *             int32 counts [B*H*nb]      kept key-blocks of each query-block
  *                                        (blocks starting at or beyond kv_len
  *                                        are dropped)
- *             int32 order  [B*H*nb]      launch order of the query-blocks
+ *             int32 order  [8*chunk]     launch plan, chunk = ceil(B*H/8)*nb:
+ *                                        segment x holds the query-blocks of
+ *                                        the (b,h) pairs with (b*H+h) % 8 == x,
+ *                                        longest kept list first, then -1
  *             int32 index  [B*H*nb*nb]   ascending kept key-blocks, row-wise;
  *                                        entries past counts[] are undefined
  *           (nb = N/block).  Each array starts at the next 256-byte boundary

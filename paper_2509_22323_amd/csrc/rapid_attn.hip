@@ -71,11 +71,11 @@ struct AttnParams {
 // ---------------------------------------------------------------------------
 // Mask compaction: one wavefront per (b, h, query-block) row of the mask.
 // counts[row] = number of kept key-blocks whose first token is below kv_len;
-// index[row*nb + 0..count) = those key-blocks, ascending; order[row] = row.
+// index[row*nb + 0..count) = those key-blocks, ascending.
 // ---------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void compact_mask_kernel(
     const unsigned char* __restrict__ mask, int rows, int nb, int block, int kv_len,
-    int32_t* __restrict__ counts, int32_t* __restrict__ order, int32_t* __restrict__ index)
+    int32_t* __restrict__ counts, int32_t* __restrict__ index)
 {
     const int lane = threadIdx.x & 63;
     const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
@@ -90,7 +90,60 @@ __global__ __launch_bounds__(256) void compact_mask_kernel(
         if (keep) irow[base + __popcll(bal & ((1ull << lane) - 1ull))] = j;
         base += __popcll(bal);
     }
-    if (lane == 0) { counts[row] = base; order[row] = row; }
+    if (lane == 0) counts[row] = base;
+}
+
+// ---------------------------------------------------------------------------
+// Launch plan of the sparse path.  Items = (b, h, query-block).  All items of one (b,h)
+// go to XCD (b*H + h) % 8, so the K/V of a head stay in one L2; inside an XCD the items
+// are ordered by kept-tile count, longest first (the dispatcher hands out workgroups in
+// id order, so this is longest-processing-time-first scheduling of a ragged batch).
+// order[x * chunk + i] = i-th item of XCD x, -1 past the end.  One workgroup per XCD:
+// counting sort over the counts (0..nb).  Items of equal count land in arbitrary order;
+// that only changes which workgroup computes an item, never its value.
+// ---------------------------------------------------------------------------
+constexpr int PLAN_MAX_NB = 8184;                // 1023 * 8 bins + bin 0 fit the scan below
+
+__global__ __launch_bounds__(1024) void plan_kernel(const int32_t* __restrict__ counts, int BH, int nb, int chunk,
+                                                    int32_t* __restrict__ order)
+{
+    __shared__ int hist[PLAN_MAX_NB + 8];        // by r = nb - count (r = 0: longest list)
+    __shared__ int scan[2][1024];
+    const int x = blockIdx.x, tid = threadIdx.x;
+    const int n_bh = (BH - x + XCDS - 1) / XCDS;  // (b,h) pairs with index % 8 == x
+    const int n_items = n_bh > 0 ? n_bh * nb : 0;
+    int32_t* out = order + (size_t)x * chunk;
+    for (int i = n_items + tid; i < chunk; i += 1024) out[i] = -1;
+    auto item_of = [&](int i) { return ((i / nb) * XCDS + x) * nb + i % nb; };
+    if (nb > PLAN_MAX_NB) {                       // no sort: natural order
+        for (int i = tid; i < n_items; i += 1024) out[i] = item_of(i);
+        return;
+    }
+    for (int r = tid; r < PLAN_MAX_NB + 8; r += 1024) hist[r] = 0;
+    __syncthreads();
+    for (int i = tid; i < n_items; i += 1024) atomicAdd(&hist[nb - counts[item_of(i)]], 1);
+    __syncthreads();
+    // exclusive prefix over r: thread t owns bins 8t .. 8t+7
+    int own[8], sum = 0;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) { own[j] = hist[8 * tid + j]; sum += own[j]; }
+    scan[0][tid] = sum;
+    __syncthreads();
+    int cur = 0;
+    for (int d = 1; d < 1024; d <<= 1) {
+        const int v = scan[cur][tid] + (tid >= d ? scan[cur][tid - d] : 0);
+        scan[cur ^ 1][tid] = v;
+        cur ^= 1;
+        __syncthreads();
+    }
+    int run = scan[cur][tid] - sum;               // exclusive
+#pragma unroll
+    for (int j = 0; j < 8; ++j) { hist[8 * tid + j] = run; run += own[j]; }
+    __syncthreads();
+    for (int i = tid; i < n_items; i += 1024) {
+        const int item = item_of(i);
+        out[atomicAdd(&hist[nb - counts[item]], 1)] = item;
+    }
 }
 
 // ---------------------------------------------------------------------------
@@ -150,113 +203,125 @@ struct SoftmaxState {
 };
 
 // ---------------------------------------------------------------------------
-// V^T fragments through the LDS transpose read.  These reads are written as inline
-// assembly with their own s_waitcnt: issued through the compiler builtin they carry no
-// alias scope, and the compiler then makes every one of them wait for ALL outstanding
-// global->LDS copies (vmcnt(0)), which would serialise the copy pipeline.  LDS returns
-// data in order, so "lgkmcnt(N)" = everything but the newest N LDS requests has arrived.
+// The matrix work of one tile as a stream of ITEMS.  An item is one MFMA together with
+// the LDS read(s) of its A operand:
+//   items 0 .. NPV-1     O^T += V^T P^T   item = (g, db): 16-key group g = 2 rb + t, 32-row
+//                        block db of O^T; two transpose reads (keys 4h+r and 8+4h+r)
+//   items NPV .. NI-1    S^T += K Q^T     item = (t, rb): k-step t, 32-key row block rb;
+//                        one 128-bit read
+// The reads of item i+PD are requested before the MFMA of item i is issued, so every
+// operand has PD MFMAs (about 200 cycles) of lead.  The reads are inline assembly with
+// their own s_waitcnt: issued through compiler builtins the transpose reads carry no
+// alias scope and each of them would wait for ALL outstanding global->LDS copies.  LDS
+// returns data in order, so "lgkmcnt(N)" = everything but the newest N requests has
+// arrived; the counter has 4 bits, which bounds PD (at most 15 requests in flight).
 // ---------------------------------------------------------------------------
 template <int D>
-struct VFrag {
-    u32x2 lo[D / 32];      // keys 4h+r      of the 16-key step, for each 32-row block of O^T
-    u32x2 hi[D / 32];      // keys 8+4h+r
+struct TileItems {
+    static constexpr int DB = D / 32, KS = D / 16;
+    static constexpr int NPV = 4 * DB;
+    static constexpr int NQK = 2 * KS;
+    static constexpr int NI = NPV + NQK;
+    static constexpr int PD = 6;
+    static constexpr int NBUF = PD + 1;
+    static constexpr int reads(int i) { return i < NPV ? 2 : 1; }
+    // LDS requests of the items after i that are in flight while item i is awaited
+    static constexpr int newer(int i, int last)
+    {
+        int s = 0;
+        for (int k = i + 1; k <= i + PD && k < last; ++k) s += reads(k);
+        return s;
+    }
 };
 
-// Request the fragments of the 16 keys starting at tile row ROW0 (a multiple of 16).
-// vaddr[db] = LDS byte address of this lane's patch in tile row 0 for O^T block db.
-template <int D, int ROW0>
-__device__ __forceinline__ void vt_request(VFrag<D>& f, const unsigned (&vaddr)[D / 32])
+template <int D>
+struct TileCtx {
+    unsigned vaddr[D / 32];                    // LDS byte address of this lane's transpose-read patch, per O^T block
+    unsigned kaddr[D / 16];                    // LDS byte address of this lane's K chunk in row n, per k-step
+    u32x2 lo[TileItems<D>::NBUF];              // item i lives in slot i % NBUF
+    u32x2 hi[TileItems<D>::NBUF];
+    u32x4 kf[TileItems<D>::NBUF];
+};
+
+template <int D, int I>
+__device__ __forceinline__ void item_request(TileCtx<D>& c)
 {
+    typedef TileItems<D> TI;
     constexpr int RB = Geo<D>::ROW_BYTES;
-#pragma unroll
-    for (int db = 0; db < D / 32; ++db) {
+    constexpr int slot = I % TI::NBUF;
+    if constexpr (I < TI::NPV) {
+        constexpr int g = I / TI::DB, db = I % TI::DB;
+        constexpr int row0 = (g >> 1) * 32 + (g & 1) * 16;
         asm volatile("ds_read_b64_tr_b16 %0, %2 offset:%3\n\tds_read_b64_tr_b16 %1, %2 offset:%4"
-                     : "=&v"(f.lo[db]), "=&v"(f.hi[db])
-                     : "v"(vaddr[db]), "i"(ROW0 * RB), "i"((ROW0 + 8) * RB));
-    }
-}
-
-// Wait until the fragments in `f` have arrived; N = newer LDS requests that may stay in
-// flight.  The fragments are in/out operands so that their uses are ordered after the wait.
-template <int D, int N>
-__device__ __forceinline__ void vt_wait(VFrag<D>& f)
-{
-    if constexpr (D == 128) {
-        asm volatile("s_waitcnt lgkmcnt(%8)"
-                     : "+v"(f.lo[0]), "+v"(f.hi[0]), "+v"(f.lo[1]), "+v"(f.hi[1]),
-                       "+v"(f.lo[2]), "+v"(f.hi[2]), "+v"(f.lo[3]), "+v"(f.hi[3])
-                     : "i"(N));
+                     : "=&v"(c.lo[slot]), "=&v"(c.hi[slot])
+                     : "v"(c.vaddr[db]), "i"(row0 * RB), "i"((row0 + 8) * RB));
     } else {
-        asm volatile("s_waitcnt lgkmcnt(%4)"
-                     : "+v"(f.lo[0]), "+v"(f.hi[0]), "+v"(f.lo[1]), "+v"(f.hi[1])
-                     : "i"(N));
+        constexpr int t = (I - TI::NPV) / 2, rb = (I - TI::NPV) % 2;
+        asm volatile("ds_read_b128 %0, %1 offset:%2" : "=&v"(c.kf[slot]) : "v"(c.kaddr[t]), "i"(rb * 32 * RB));
     }
 }
 
-// Products of one 16-key group G = 2 rb + t; requests the fragments of group G+1 first.
-// NEWER = LDS requests issued after the fragments of this group that may stay in flight.
-template <int D, int GRP, int NEWER = 0>
-__device__ __forceinline__ void pv_group(VFrag<D> (&vfrag)[2], const unsigned (&vaddr)[D / 32],
-                                         const bf16x8 (&pb)[4], f32x16 (&acc)[D / 32])
+// Wait for item I; LAST = end of the run of items whose requests may be in flight.  The
+// fragment is an in/out operand so that its use is ordered after the wait.
+template <int D, int I, int LAST>
+__device__ __forceinline__ void item_wait(TileCtx<D>& c)
 {
-    if constexpr (GRP < 3) {
-        vt_request<D, ((GRP + 1) >> 1) * 32 + ((GRP + 1) & 1) * 16>(vfrag[(GRP + 1) & 1], vaddr);
-        vt_wait<D, 2 * (D / 32) + NEWER>(vfrag[GRP & 1]);
+    typedef TileItems<D> TI;
+    constexpr int slot = I % TI::NBUF;
+    constexpr int N = TI::newer(I, LAST);
+    static_assert(N + TI::reads(I) <= 15, "lgkmcnt is a 4-bit counter");
+    if constexpr (I < TI::NPV) asm volatile("s_waitcnt lgkmcnt(%2)" : "+v"(c.lo[slot]), "+v"(c.hi[slot]) : "i"(N));
+    else asm volatile("s_waitcnt lgkmcnt(%1)" : "+v"(c.kf[slot]) : "i"(N));
+}
+
+template <int D, int I>
+__device__ __forceinline__ void item_mfma(const TileCtx<D>& c, const bf16x8 (&pb)[4], const bf16x8 (&qf)[D / 16],
+                                          f32x16 (&acc)[D / 32], f32x16 (&st)[2])
+{
+    typedef TileItems<D> TI;
+    constexpr int slot = I % TI::NBUF;
+    if constexpr (I < TI::NPV) {
+        constexpr int g = I / TI::DB, db = I % TI::DB;
+        const u32x4 both = __builtin_shufflevector(c.lo[slot], c.hi[slot], 0, 1, 2, 3);
+        acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, both), pb[g], acc[db], 0, 0, 0);
     } else {
-        vt_wait<D, NEWER>(vfrag[GRP & 1]);
-    }
+        constexpr int t = (I - TI::NPV) / 2, rb = (I - TI::NPV) % 2;
+        f32x16 cin = st[rb];
+        if constexpr (t == 0) {                            // first k-step starts from zero
 #pragma unroll
-    for (int db = 0; db < D / 32; ++db) {
-        const u32x4 both = __builtin_shufflevector(vfrag[GRP & 1].lo[db], vfrag[GRP & 1].hi[db], 0, 1, 2, 3);
-        acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, both), pb[GRP], acc[db], 0, 0, 0);
+            for (int j = 0; j < 16; ++j) cin[j] = 0.f;
+        }
+        st[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, c.kf[slot]), qf[t], cin, 0, 0, 0);
     }
 }
 
-// K fragments (A operand of S^T = K Q^T), requested in batches of two k-steps x two row
-// blocks = 4 x ds_read_b128, through assembly with explicit waits for the same reason as the
-// V^T fragments: batch b+1 is in flight while the four products of batch b are issued.
-struct KBatch {
-    u32x4 f[4];            // [2 * (t & 1) + rb]
-};
-
-// kaddr[t] = LDS byte address of this lane's 16-byte chunk of k-step t in row n of the tile.
-template <int D, int B>
-__device__ __forceinline__ void k_request(KBatch& kb, const unsigned (&kaddr)[D / 16])
+// Request the first PD items of the run [FROM, TO).
+template <int D, int FROM, int TO, int I = FROM>
+__device__ __forceinline__ void items_prefetch(TileCtx<D>& c)
 {
-    constexpr int RB32 = 32 * Geo<D>::ROW_BYTES;           // second 32-key row block
-    asm volatile("ds_read_b128 %0, %4\n\tds_read_b128 %1, %4 offset:%6\n\t"
-                 "ds_read_b128 %2, %5\n\tds_read_b128 %3, %5 offset:%6"
-                 : "=&v"(kb.f[0]), "=&v"(kb.f[1]), "=&v"(kb.f[2]), "=&v"(kb.f[3])
-                 : "v"(kaddr[2 * B]), "v"(kaddr[2 * B + 1]), "i"(RB32));
-}
-
-template <bool MORE>
-__device__ __forceinline__ void k_wait(KBatch& kb)
-{
-    asm volatile("s_waitcnt lgkmcnt(%4)"
-                 : "+v"(kb.f[0]), "+v"(kb.f[1]), "+v"(kb.f[2]), "+v"(kb.f[3])
-                 : "i"(MORE ? 4 : 0));
-}
-
-template <int D, int B>
-__device__ __forceinline__ void qk_batch(KBatch (&kb)[2], const unsigned (&kaddr)[D / 16],
-                                         const bf16x8 (&qf)[D / 16], f32x16 (&st)[2])
-{
-    constexpr int NB = D / 32;                             // batches per tile
-    if constexpr (B + 1 < NB) {
-        k_request<D, B + 1>(kb[(B + 1) & 1], kaddr);
-        k_wait<true>(kb[B & 1]);
-    } else {
-        k_wait<false>(kb[B & 1]);
+    if constexpr (I < TO && I < FROM + TileItems<D>::PD) {
+        item_request<D, I>(c);
+        items_prefetch<D, FROM, TO, I + 1>(c);
     }
-#pragma unroll
-    for (int tt = 0; tt < 2; ++tt)
-#pragma unroll
-        for (int rb = 0; rb < 2; ++rb)
-            st[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kb[B & 1].f[2 * tt + rb]),
-                                                             qf[2 * B + tt], st[rb], 0, 0, 0);
 }
 
+// Issue items [I, TO); items_prefetch<D, I, TO> must have been called before.
+template <int D, int I, int TO>
+__device__ __forceinline__ void items_run(TileCtx<D>& c, const bf16x8 (&pb)[4], const bf16x8 (&qf)[D / 16],
+                                          f32x16 (&acc)[D / 32], f32x16 (&st)[2])
+{
+    if constexpr (I < TO) {
+        if constexpr (I + TileItems<D>::PD < TO) item_request<D, I + TileItems<D>::PD>(c);
+        item_wait<D, I, TO>(c);
+        item_mfma<D, I>(c, pb, qf, acc, st);
+        items_run<D, I + 1, TO>(c, pb, qf, acc, st);
+    }
+}
+
+// Lane addresses for the tile held in (lds_k, lds_v).
+//   K: lane (n, h) reads row n (+32 rb), logical chunk 2t + h of k-step t.
+//   V: within a 16-lane group, lane j points at row j/4, columns 4 (j%4)..+3 of a 4 x 16
+//      patch of the transpose read and lane i receives column i; lane half h covers rows +4h.
 template <int D>
 __device__ __forceinline__ void k_addresses(const char* lds_k, int n, int h, unsigned (&kaddr)[D / 16])
 {
@@ -267,23 +332,20 @@ __device__ __forceinline__ void k_addresses(const char* lds_k, int n, int h, uns
     for (int t = 0; t < D / 16; ++t) kaddr[t] = kbase + (((2 * t) ^ kx) << 4);
 }
 
-// S^T = K Q^T for one 64-key tile: two 32-key row blocks; keys at or beyond kv_len -> -inf.
-// Register i of row block rb holds key  key0 + 32 rb + 8 (i/4) + 4 h + i%4  of query n.
-// Batch 0 of the K fragments must already have been requested into kb[0].
 template <int D>
-__device__ __forceinline__ void qk_tile(KBatch (&kb)[2], const unsigned (&kaddr)[D / 16], const bf16x8 (&qf)[D / 16],
-                                        f32x16 (&st)[2], int key0, int kv_len, int h)
+__device__ __forceinline__ void v_addresses(const char* lds_v, int h, int tr_row, int tr_col, unsigned (&vaddr)[D / 32])
 {
+    typedef Geo<D> G;
+    const unsigned vbase = (unsigned)(size_t)LDS_PTR(const char, lds_v) + (4 * h + tr_row) * G::ROW_BYTES + tr_col * 2;
+    const int vx = G::swz_v(tr_row) >> 2;                  // 64-byte group swizzle of this lane's rows
 #pragma unroll
-    for (int rb = 0; rb < 2; ++rb)
-#pragma unroll
-        for (int j = 0; j < 16; ++j) st[rb][j] = 0.f;
-    qk_batch<D, 0>(kb, kaddr, qf, st);
-    qk_batch<D, 1>(kb, kaddr, qf, st);
-    if constexpr (D == 128) {
-        qk_batch<D, 2>(kb, kaddr, qf, st);
-        qk_batch<D, 3>(kb, kaddr, qf, st);
-    }
+    for (int db = 0; db < D / 32; ++db) vaddr[db] = vbase + ((db ^ vx) << 6);
+}
+
+// Keys at or beyond kv_len -> -inf.  Register i of row block rb of S^T holds key
+// key0 + 32 rb + 8 (i/4) + 4 h + i%4  of query n.
+__device__ __forceinline__ void mask_tail(f32x16 (&st)[2], int key0, int kv_len, int h)
+{
     if (key0 + KT > kv_len) {
 #pragma unroll
         for (int rb = 0; rb < 2; ++rb)
@@ -338,49 +400,24 @@ __device__ __forceinline__ void softmax_tile(const f32x16 (&st)[2], f32x16 (&acc
     st_.l += rs0 + rs1;
 }
 
-// LDS byte addresses of this lane's transpose-read patches in row 0 of a V tile.
-template <int D>
-__device__ __forceinline__ void v_addresses(const char* lds_v, int h, int tr_row, int tr_col, unsigned (&vaddr)[D / 32])
-{
-    typedef Geo<D> G;
-    const unsigned vbase = (unsigned)(size_t)LDS_PTR(const char, lds_v) + (4 * h + tr_row) * G::ROW_BYTES + tr_col * 2;
-    const int vx = G::swz_v(tr_row) >> 2;                  // 64-byte group swizzle of this lane's rows
-#pragma unroll
-    for (int db = 0; db < D / 32; ++db) vaddr[db] = vbase + ((db ^ vx) << 6);
-}
-
-// O^T += V^T P^T for one tile.  Four groups (rb, t) of 16 keys; the V^T fragments of group
-// g+1 are requested before the products of group g are issued; group 0 must already have
-// been requested into vfrag[0].
-template <int D>
-__device__ __forceinline__ void pv_tile(VFrag<D> (&vfrag)[2], const unsigned (&vaddr)[D / 32],
-                                        const bf16x8 (&pb)[4], f32x16 (&acc)[D / 32])
-{
-    pv_group<D, 0>(vfrag, vaddr, pb, acc);
-    pv_group<D, 1>(vfrag, vaddr, pb, acc);
-    pv_group<D, 2>(vfrag, vaddr, pb, acc);
-    pv_group<D, 3>(vfrag, vaddr, pb, acc);
-}
-
 // One 64-key tile in sequence: S^T = K Q^T, online softmax, O^T += V^T P^T.
 template <int D>
 __device__ __forceinline__ void compute_tile(const char* lds_k, const char* lds_v, const bf16x8 (&qf)[D / 16],
                                              f32x16 (&acc)[D / 32], SoftmaxState& st_, int key0, int kv_len,
                                              float c, float tau, int n, int h, int tr_row, int tr_col)
 {
-    unsigned kaddr[D / 16];
-    k_addresses<D>(lds_k, n, h, kaddr);
-    KBatch kb[2];
-    k_request<D, 0>(kb[0], kaddr);
-    f32x16 st[2];
-    qk_tile<D>(kb, kaddr, qf, st, key0, kv_len, h);
-    unsigned vaddr[D / 32];
-    v_addresses<D>(lds_v, h, tr_row, tr_col, vaddr);
-    VFrag<D> vfrag[2];
-    vt_request<D, 0>(vfrag[0], vaddr);                     // consumed after the softmax
+    typedef TileItems<D> TI;
+    TileCtx<D> ctx;
+    k_addresses<D>(lds_k, n, h, ctx.kaddr);
+    v_addresses<D>(lds_v, h, tr_row, tr_col, ctx.vaddr);
     bf16x8 pb[4];
+    f32x16 st[2];
+    items_prefetch<D, TI::NPV, TI::NI>(ctx);
+    items_run<D, TI::NPV, TI::NI>(ctx, pb, qf, acc, st);
+    mask_tail(st, key0, kv_len, h);
+    items_prefetch<D, 0, TI::NPV>(ctx);                    // first V^T fragments: consumed after the softmax
     softmax_tile<D>(st, acc, st_, c, tau, pb);
-    pv_tile<D>(vfrag, vaddr, pb, acc);
+    items_run<D, 0, TI::NPV>(ctx, pb, qf, acc, st);
 }
 
 // Epilogue: O = acc / l as bf16.  Register 4j+r of block db holds d = 32 db + 8 j + 4 h + r
@@ -464,7 +501,6 @@ __global__ __launch_bounds__(64 * NW, WPE) void attn_kernel(const AttnParams p)
     const int wg = blockIdx.x;
     int item = (wg % XCDS) * p.chunk + wg / XCDS;
     if (item >= p.items) return;
-    if (p.order) item = ((const __attribute__((address_space(4))) int32_t*)p.order)[item];
     const int bh = item / p.nq;
     const int qi = item % p.nq;
 
@@ -677,14 +713,14 @@ __global__ __launch_bounds__(512, 2) void attn_dense_pp_kernel(const AttnParams 
     __syncthreads();
     if (group == 1) __syncthreads();              // group 1 runs one barrier behind
 
+    typedef TileItems<D> TI;
+    TileCtx<D> ctx;
+    bf16x8 pb[4];
     f32x16 st[2];
-    {
-        unsigned kaddr[KS];
-        k_addresses<D>(stage_k(0), n, h, kaddr);
-        KBatch kb[2];
-        k_request<D, 0>(kb[0], kaddr);
-        qk_tile<D>(kb, kaddr, qf, st, 0, kv_len, h);
-    }
+    k_addresses<D>(stage_k(0), n, h, ctx.kaddr);
+    items_prefetch<D, TI::NPV, TI::NI>(ctx);
+    items_run<D, TI::NPV, TI::NI>(ctx, pb, qf, acc, st);   // S_0
+    mask_tail(st, 0, kv_len, h);
 
     for (int j0 = 0; j0 < T; j0 += 4) {
 #pragma unroll
@@ -697,13 +733,10 @@ __global__ __launch_bounds__(512, 2) void attn_dense_pp_kernel(const AttnParams 
             phase_barrier();
 
             // ---- B(j)
-            unsigned vaddr[DB];
-            v_addresses<D>(stage_v(s), h, tr_row, tr_col, vaddr);
-            bf16x8 pb[4];
+            v_addresses<D>(stage_v(s), h, tr_row, tr_col, ctx.vaddr);
             softmax_tile<D>(st, acc, sm, p.c, tau, pb);
             pin_in_phase(pb, sm.l);
-            VFrag<D> vfrag[2];
-            vt_request<D, 0>(vfrag[0], vaddr);
+            items_prefetch<D, 0, TI::NI>(ctx);             // first V^T fragments of A(j)
             phase_barrier();
 
             // ---- A(j): matrix work first in line at the SIMD's issue arbiter
@@ -712,24 +745,210 @@ __global__ __launch_bounds__(512, 2) void attn_dense_pp_kernel(const AttnParams 
                 issue_tile<D, NW, false>(K, (j + 3) * KT, kv_len, stage_k((s + 3) & 3), wave, lane);
                 issue_tile<D, NW, true>(V, (j + 3) * KT, kv_len, stage_v((s + 3) & 3), wave, lane);
             }
-            // (the first K fragments of tile j+1 are requested ahead of the last PV products;
-            // for the last tile this re-reads a landed stage and the result is dropped)
-            unsigned kaddr[KS];
-            k_addresses<D>(stage_k((j + 1 < T) ? ((s + 1) & 3) : s), n, h, kaddr);
-            KBatch kb[2];
-            pv_group<D, 0>(vfrag, vaddr, pb, acc);
-            pv_group<D, 1>(vfrag, vaddr, pb, acc);
-            pv_group<D, 2>(vfrag, vaddr, pb, acc);
-            k_request<D, 0>(kb[0], kaddr);
-            pv_group<D, 3, 4>(vfrag, vaddr, pb, acc);
-            if (j + 1 < T) qk_tile<D>(kb, kaddr, qf, st, (j + 1) * KT, kv_len, h);
-            else k_wait<false>(kb[0]);
+            // PV(j) then QK(j+1) as one stream.  For the last tile the QK half re-reads a
+            // landed stage and its result is never used.
+            k_addresses<D>(stage_k((j + 1 < T) ? ((s + 1) & 3) : s), n, h, ctx.kaddr);
+            items_run<D, 0, TI::NI>(ctx, pb, qf, acc, st);
+            mask_tail(st, (j + 1) * KT, kv_len, h);
             __builtin_amdgcn_s_setprio(0);
         }
     }
     if (group == 0) __syncthreads();              // same number of barriers for every wavefront
 
     write_output<D>(O, acc, sm.l, qrow, qvalid, p.N, h);
+}
+
+// ---------------------------------------------------------------------------
+// Sparse path: one workgroup per (b, h, query-block); its kept-tile list is split between
+// two wavefront groups (even tiles -> group 0, odd tiles -> group 1) that work on the SAME
+// queries with separate softmax states and are merged through LDS at the end.  This halves
+// the critical path of a long list (a text row keeps every tile) and gives the same
+// anti-phase pairing of softmax and MFMA phases as the dense path.
+//
+// Time is divided into slots by workgroup barriers; tile t (64 keys) is handled as
+//   slot t      S_t = K_t Q^T          (inside the A phase of tile t-2, or alone for t = 0, 1)
+//   slot t+1    B(t): softmax of S_t, first V_t^T fragments requested
+//   slot t+2    A(t): O^T += V_t^T P_t^T ; S_{t+2}
+// by group t % 2, so in every slot one group is in an A phase and the other in a B phase.
+// Every wavefront passes T+2 slot barriers (a group without work in a slot only does its
+// share of the copies and waits).  Copies: in slot s every wavefront issues its share of
+// K_{s+3} (4-stage ring) and V_{s+2} (5-stage ring) and, before the barrier that ends the
+// slot, waits for its share of K_{s+1} and V_s (both issued in slot s-2; copies complete
+// in order).  K_t is therefore complete at the start of slot t and V_t at the start of
+// slot t+1; stage reuse: K_{t+4} is issued in slot t+1 > t, V_{t+5} in slot t+3 > t+2.
+// All LDS traffic of the main loop is explicit assembly, so stages are plain runtime
+// offsets into one array.
+// ---------------------------------------------------------------------------
+template <int D, int WPG>
+__global__ __launch_bounds__(128 * WPG, 2) void attn_sparse_pp_kernel(const AttnParams p)
+{
+    typedef Geo<D> G;
+    typedef TileItems<D> TI;
+    constexpr int NW = 2 * WPG, QT = 32 * WPG, KS = D / 16, DB = D / 32;
+    constexpr int NSK = 4, NSV = 5;
+    constexpr int LPT = 2 * G::LOADS / NW;        // copy instructions per wavefront per slot (K + V)
+    static_assert(WPG * DB * 16 * 64 * 4 + WPG * 64 * 8 <= (NSK + NSV) * G::TILE_BYTES, "merge buffer fits the rings");
+
+    __shared__ __attribute__((aligned(1024))) char lds[(NSK + NSV) * G::TILE_BYTES];
+
+    typedef const __attribute__((address_space(4))) int32_t* cptr_t;
+    const int wg = blockIdx.x;
+    const int item = ((cptr_t)p.order)[(size_t)(wg % XCDS) * p.chunk + wg / XCDS];
+    if (item < 0) return;
+    const int bh = item / p.nq;
+    const int qi = item % p.nq;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int group = wave / WPG;
+    const int wq = wave % WPG;
+    const int n = lane & 31;
+    const int h = lane >> 5;
+    const int kv_len = p.kv_len;
+
+    const size_t base = (size_t)bh * p.N * D;
+    const __bf16* __restrict__ Q = p.q + base;
+    const __bf16* __restrict__ K = p.k + base;
+    const __bf16* __restrict__ V = p.v + base;
+    __bf16* __restrict__ O = p.o + base;
+
+    const int qrow = qi * QT + wq * 32 + n;       // groups share the queries
+    const bool qvalid = qrow < kv_len;
+
+    // 64-key tiles of this item: tile t -> first key
+    const int ss = p.sub_shift;
+    cptr_t list = (cptr_t)(p.index + (size_t)item * p.nb);
+    int T;
+    {
+        const int n_blocks = ((cptr_t)p.counts)[item];
+        T = n_blocks << ss;
+        if (n_blocks > 0 && (((list[n_blocks - 1] + 1) << ss) - 1) * KT >= kv_len) T -= 1;
+    }
+    f32x16 acc[DB];
+#pragma unroll
+    for (int i = 0; i < DB; ++i)
+#pragma unroll
+        for (int j = 0; j < 16; ++j) acc[i][j] = 0.f;
+    if (T <= 0) {                                 // nothing kept: the rows are zero
+        if (group == 0) write_output<D>(O, acc, 0.f, qrow, false, p.N, h);
+        return;
+    }
+    auto key_of = [&](int t) -> int { return ((list[t >> ss] << ss) + (t & ((1 << ss) - 1))) * KT; };
+    auto k_stage = [&](int t) -> char* { return lds + (t & (NSK - 1)) * G::TILE_BYTES; };
+    // kq[i] = first key of tile s+i for the current slot s (0 past the end); kq4 is loaded a slot ahead
+    int kq[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) kq[i] = (i < T) ? key_of(i) : 0;
+    int kq4 = (4 < T) ? key_of(4) : 0;
+    int vst_issue = 2;                            // V stage of tile s+2
+    int vst_use = 0;                              // V stage of this group's current tile
+
+    // prologue: K_0..K_2, V_0, V_1
+#pragma unroll
+    for (int t = 0; t < 3; ++t)
+        if (t < T) issue_tile<D, NW, false>(K, kq[t], kv_len, k_stage(t), wave, lane);
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+        if (t < T) issue_tile<D, NW, true>(V, kq[t], kv_len, lds + (NSK + t) * G::TILE_BYTES, wave, lane);
+
+    bf16x8 qf[KS];
+    load_q<D>(Q, qrow, qvalid, h, qf);
+    SoftmaxState sm;
+    sm.m = -INFINITY;
+    sm.l = 0.f;
+    const float tau = 8.0f / p.c;
+    const int tr_row = (lane & 15) >> 2;
+    const int tr_col = ((lane & 3) << 2) + (((lane >> 4) & 1) << 4);
+    wait_vmcnt<0>();
+    __syncthreads();
+
+    int s = 0;                                    // current slot = slot barriers passed
+    auto slot_begin = [&]() {                     // my share of K_{s+3} and V_{s+2}
+        if (s + 3 < T) issue_tile<D, NW, false>(K, kq[3], kv_len, k_stage(s + 3), wave, lane);
+        if (s + 2 < T) issue_tile<D, NW, true>(V, kq[2], kv_len, lds + (NSK + vst_issue) * G::TILE_BYTES, wave, lane);
+    };
+    auto slot_end = [&]() {                       // K_{s+1} and V_s complete, then the barrier
+        if (s + 3 < T) wait_vmcnt<2 * LPT>();
+        else wait_vmcnt<0>();
+        phase_barrier();
+        ++s;
+        kq[0] = kq[1]; kq[1] = kq[2]; kq[2] = kq[3]; kq[3] = kq4;
+        kq4 = (s + 4 < T) ? key_of(s + 4) : 0;
+        vst_issue = (vst_issue == NSV - 1) ? 0 : vst_issue + 1;
+    };
+
+    TileCtx<D> ctx;
+    bf16x8 pb[4];
+    f32x16 st[2];
+
+    if (group == 1) { slot_begin(); slot_end(); vst_use = 1; }   // group 1 runs one slot behind
+    int t = group;                                // this group's tiles: group, group + 2, ...
+    if (t < T) {                                  // slot t: S_t on its own
+        slot_begin();
+        k_addresses<D>(k_stage(t), n, h, ctx.kaddr);
+        items_prefetch<D, TI::NPV, TI::NI>(ctx);
+        items_run<D, TI::NPV, TI::NI>(ctx, pb, qf, acc, st);
+        mask_tail(st, kq[0], kv_len, h);
+        slot_end();
+    }
+    while (t < T) {
+        // ---- slot t+1: B(t)
+        slot_begin();
+        v_addresses<D>(lds + (NSK + vst_use) * G::TILE_BYTES, h, tr_row, tr_col, ctx.vaddr);
+        softmax_tile<D>(st, acc, sm, p.c, tau, pb);
+        pin_in_phase(pb, sm.l);
+        items_prefetch<D, 0, TI::NI>(ctx);        // first V_t^T fragments of A(t)
+        slot_end();
+        // ---- slot t+2: A(t)
+        __builtin_amdgcn_s_setprio(3);
+        slot_begin();
+        // (without a tile t+2 the QK half re-reads K_t, which is landed, and is dropped)
+        k_addresses<D>(k_stage((t + 2 < T) ? t + 2 : t), n, h, ctx.kaddr);
+        items_run<D, 0, TI::NI>(ctx, pb, qf, acc, st);
+        mask_tail(st, kq[0], kv_len, h);
+        __builtin_amdgcn_s_setprio(0);
+        slot_end();
+        t += 2;
+        vst_use += 2;
+        if (vst_use >= NSV) vst_use -= NSV;
+    }
+    while (s < T + 2) { slot_begin(); slot_end(); }
+
+    // ---- merge the two groups (same queries, same register layout) through LDS
+    u32x4* mbuf = (u32x4*)lds;                                    // [wq][DB*4][64 lanes]
+    float* mlbuf = (float*)(lds + WPG * DB * 4 * 64 * 16);        // [wq][64 lanes][m, l]
+    if (group == 1) {
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                u32x4 v;
+#pragma unroll
+                for (int r = 0; r < 4; ++r) v[r] = __float_as_uint(acc[db][4 * j + r]);
+                mbuf[(wq * DB * 4 + db * 4 + j) * 64 + lane] = v;
+            }
+        mlbuf[(wq * 64 + lane) * 2] = sm.m;
+        mlbuf[(wq * 64 + lane) * 2 + 1] = sm.l;
+    }
+    __syncthreads();
+    if (group == 0) {
+        const float m1 = mlbuf[(wq * 64 + lane) * 2];
+        const float l1 = mlbuf[(wq * 64 + lane) * 2 + 1];
+        const float m = fmaxf(sm.m, m1);                          // group 0 always has tile 0: finite
+        const float a0 = __builtin_amdgcn_exp2f((sm.m - m) * p.c);
+        const float a1 = __builtin_amdgcn_exp2f((m1 - m) * p.c);  // 0 if group 1 had no tile
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const u32x4 v = mbuf[(wq * DB * 4 + db * 4 + j) * 64 + lane];
+#pragma unroll
+                for (int r = 0; r < 4; ++r)
+                    acc[db][4 * j + r] = acc[db][4 * j + r] * a0 + __uint_as_float(v[r]) * a1;
+            }
+        write_output<D>(O, acc, sm.l * a0 + l1 * a1, qrow, qvalid, p.N, h);
+    }
 }
 
 // ---------------------------------------------------------------------------
@@ -741,6 +960,9 @@ struct WorkspaceLayout {
     size_t counts_off, order_off, index_off, total;
 };
 
+// items of one XCD in the launch plan: (b,h) pairs are dealt round-robin over the XCDs
+inline int plan_chunk(int B, int H, int nb) { return ((B * H + XCDS - 1) / XCDS) * nb; }
+
 inline WorkspaceLayout workspace_layout(int B, int H, int nb)
 {
     const size_t rows = (size_t)B * H * nb;
@@ -748,7 +970,7 @@ inline WorkspaceLayout workspace_layout(int B, int H, int nb)
     WorkspaceLayout w;
     w.counts_off = 0;
     w.order_off = up(rows * 4);
-    w.index_off = w.order_off + up(rows * 4);
+    w.index_off = w.order_off + up((size_t)XCDS * plan_chunk(B, H, nb) * 4);
     w.total = w.index_off + up(rows * (size_t)nb * 4);
     return w;
 }
@@ -824,7 +1046,7 @@ int rapid_attn_block_sparse(const void* q, const void* k, const void* v, void* o
     if (N % block != 0) return RAPID_ERR_SHAPE;
     const int nb = N / block;
     const long long rows = (long long)B * H * nb;
-    if (rows > 0x7fffffffLL / 2) return RAPID_ERR_SHAPE;
+    if (rows > 0x7fffffffLL / 16) return RAPID_ERR_SHAPE;
     const WorkspaceLayout w = workspace_layout(B, H, nb);
     if (!workspace || workspace_bytes < w.total) return RAPID_ERR_WORKSPACE;
     if (!aligned16(workspace)) return RAPID_ERR_ALIGN;
@@ -837,7 +1059,10 @@ int rapid_attn_block_sparse(const void* q, const void* k, const void* v, void* o
     hipStream_t s = (hipStream_t)stream;
 
     hipLaunchKernelGGL(compact_mask_kernel, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, s,
-                       mask, (int)rows, nb, block, kv_len, counts, order, index);
+                       mask, (int)rows, nb, block, kv_len, counts, index);
+    if (hipGetLastError() != hipSuccess) return RAPID_ERR_DEVICE;
+    const int chunk = plan_chunk(B, H, nb);
+    hipLaunchKernelGGL(plan_kernel, dim3(XCDS), dim3(1024), 0, s, counts, B * H, nb, chunk, order);
     if (hipGetLastError() != hipSuccess) return RAPID_ERR_DEVICE;
 
     AttnParams p{};
@@ -846,12 +1071,18 @@ int rapid_attn_block_sparse(const void* q, const void* k, const void* v, void* o
     p.H = H; p.N = N; p.kv_len = kv_len;
     p.nq = nb;
     p.items = (int)rows;
-    p.chunk = (p.items + XCDS - 1) / XCDS;
+    p.chunk = chunk;
     p.block = block; p.nb = nb; p.sub_shift = block == 128 ? 1 : 0;
     p.c = scale * LOG2E;
-    if (block == 128)
-        return D == 64 ? launch_attn<64, 4, 2, 2>(p, s) : launch_attn<128, 4, 2, 2>(p, s);
-    return D == 64 ? launch_attn<64, 2, 2, 2>(p, s) : launch_attn<128, 2, 2, 1>(p, s);
+    const dim3 grid((unsigned)chunk * XCDS);
+    if (block == 128) {
+        if (D == 64) hipLaunchKernelGGL((attn_sparse_pp_kernel<64, 4>), grid, dim3(512), 0, s, p);
+        else hipLaunchKernelGGL((attn_sparse_pp_kernel<128, 4>), grid, dim3(512), 0, s, p);
+    } else {
+        if (D == 64) hipLaunchKernelGGL((attn_sparse_pp_kernel<64, 2>), grid, dim3(256), 0, s, p);
+        else hipLaunchKernelGGL((attn_sparse_pp_kernel<128, 2>), grid, dim3(256), 0, s, p);
+    }
+    return hipGetLastError() == hipSuccess ? RAPID_OK : RAPID_ERR_DEVICE;
 }
 
 size_t rapid_attn_workspace_bytes(int B, int H, int N, int D, int block)
@@ -860,7 +1091,7 @@ size_t rapid_attn_workspace_bytes(int B, int H, int N, int D, int block)
     if (D != 64 && D != 128) return 0;
     if (block != 64 && block != 128) return 0;
     if (N % block != 0 || N > (1 << 22)) return 0;
-    if ((long long)B * H * (N / block) > 0x7fffffffLL / 2) return 0;
+    if ((long long)B * H * (N / block) > 0x7fffffffLL / 16) return 0;
     return workspace_layout(B, H, N / block).total;
 }
 

@@ -82,11 +82,15 @@ def test_deterministic_and_batch_invariant():
     assert not np.array_equal(c[1], a[1])
 
 
-def test_all_ones_mask_equals_dense_bitwise():
+def test_all_ones_mask_equals_dense():
+    """Action 0 and an all-ones mask are the same function; the two entry points sum the
+    keys in a different order, so they agree to rounding, not bit for bit."""
     for (N, D, block, kv_len) in [(512, 64, 64, 450), (512, 128, 128, 512), (384, 64, 128, 300)]:
         q, k, v = wl.make_qkv(1, 2, N, D, kv_len, seed=207)
         ones = np.ones((1, 2, N // block, N // block), np.uint8)
-        np.testing.assert_array_equal(run_sparse(q, k, v, ones, block, kv_len), run_dense(q, k, v, kv_len))
+        a, b = run_sparse(q, k, v, ones, block, kv_len), run_dense(q, k, v, kv_len)
+        assert_close(a, widen(b), "all-ones vs dense")
+        assert np.abs(widen(a) - widen(b)).max() <= 2 ** -8          # a bf16 ulp or two at |O| < 1
 
 
 def test_runs_on_a_side_stream_without_sync_inside():
