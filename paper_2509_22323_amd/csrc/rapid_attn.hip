@@ -45,7 +45,7 @@ constexpr int XCDS = 8;         // L2 domains the dispatcher deals workgroups ov
 #define DENSE_NS 3              // LDS stages on the dense path
 #endif
 #ifndef DENSE_PINGPONG
-#define DENSE_PINGPONG 1        // dense path: two wavefront groups held in anti-phase
+#define DENSE_PINGPONG 1        // dense path: 1 = softmax/MFMA phases in anti-phase, 2 = balanced phases, 0 = free-running
 #endif
 constexpr float LOG2E = 1.44269504088896340736f;
 
@@ -179,21 +179,35 @@ __device__ __forceinline__ void issue_tile(const __bf16* __restrict__ src, int k
 {
     typedef Geo<D> G;
     constexpr int PER_WAVE = G::LOADS / NW;
+    // global_load_lds_dwordx4: LDS address = M0 + 16 * lane.  Written as assembly so that the
+    // copy pipeline is ordered only by the explicit vmcnt waits and barriers of the main loop
+    // (the compiler would otherwise wait for all copies before LDS reads it cannot
+    // disambiguate).  M0 has no other user in these kernels.
+    if (key0 + KT <= kv_len) {
+        // whole tile valid: scalar tile base + a per-lane byte offset that does not depend
+        // on the tile (no vector arithmetic per copy)
+        const char* tile = (const char*)(src + (size_t)key0 * D);
 #pragma unroll
-    for (int i = 0; i < PER_WAVE; ++i) {
-        const int ld = wave * PER_WAVE + i;                 // wave-uniform
-        const int row = ld * G::ROWS_PER_LOAD + lane / G::CPR;
-        const int phys = lane % G::CPR;
-        const int logical = phys ^ (IS_V ? G::swz_v(row) : G::swz_k(row));
-        int grow = key0 + row;
-        grow = grow < kv_len ? grow : kv_len - 1;
-        const __bf16* g = src + (size_t)grow * D + logical * 8;
-        // global_load_lds_dwordx4: LDS address = M0 + 16 * lane.  Written as assembly so that
-        // the copy pipeline is ordered only by the explicit vmcnt waits and barriers of the
-        // main loop (the compiler would otherwise wait for all copies before LDS reads it
-        // cannot disambiguate).  M0 has no other user in this kernel.
-        const unsigned dst = (unsigned)(size_t)LDS_PTR(char, lds + ld * 1024);
-        asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(dst), "v"(g));
+        for (int i = 0; i < PER_WAVE; ++i) {
+            const int ld = wave * PER_WAVE + i;             // wave-uniform
+            const int row = ld * G::ROWS_PER_LOAD + lane / G::CPR;
+            const int logical = (lane % G::CPR) ^ (IS_V ? G::swz_v(row) : G::swz_k(row));
+            const unsigned off = (unsigned)(row * D + logical * 8) * 2u;
+            const unsigned dst = (unsigned)(size_t)LDS_PTR(char, lds + ld * 1024);
+            asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(dst), "v"(off), "s"(tile));
+        }
+    } else {
+#pragma unroll
+        for (int i = 0; i < PER_WAVE; ++i) {
+            const int ld = wave * PER_WAVE + i;
+            const int row = ld * G::ROWS_PER_LOAD + lane / G::CPR;
+            const int logical = (lane % G::CPR) ^ (IS_V ? G::swz_v(row) : G::swz_k(row));
+            int grow = key0 + row;
+            grow = grow < kv_len ? grow : kv_len - 1;
+            const __bf16* g = src + (size_t)grow * D + logical * 8;
+            const unsigned dst = (unsigned)(size_t)LDS_PTR(char, lds + ld * 1024);
+            asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(dst), "v"(g));
+        }
     }
 }
 
@@ -237,7 +251,8 @@ struct TileItems {
 template <int D>
 struct TileCtx {
     unsigned vaddr[D / 32];                    // LDS byte address of this lane's transpose-read patch, per O^T block
-    unsigned kaddr[D / 16];                    // LDS byte address of this lane's K chunk in row n, per k-step
+    unsigned kbase;                            // LDS byte address of row n of the K tile
+    unsigned kxor;                             // (h ^ swz_k(n)) << 4: chunk (2t+h) ^ swz == (2t) ^ (kxor >> 4)
     u32x2 lo[TileItems<D>::NBUF];              // item i lives in slot i % NBUF
     u32x2 hi[TileItems<D>::NBUF];
     u32x4 kf[TileItems<D>::NBUF];
@@ -257,7 +272,8 @@ __device__ __forceinline__ void item_request(TileCtx<D>& c)
                      : "v"(c.vaddr[db]), "i"(row0 * RB), "i"((row0 + 8) * RB));
     } else {
         constexpr int t = (I - TI::NPV) / 2, rb = (I - TI::NPV) % 2;
-        asm volatile("ds_read_b128 %0, %1 offset:%2" : "=&v"(c.kf[slot]) : "v"(c.kaddr[t]), "i"(rb * 32 * RB));
+        const unsigned ka = c.kbase + ((unsigned)(t << 5) ^ c.kxor);
+        asm volatile("ds_read_b128 %0, %1 offset:%2" : "=&v"(c.kf[slot]) : "v"(ka), "i"(rb * 32 * RB));
     }
 }
 
@@ -323,13 +339,11 @@ __device__ __forceinline__ void items_run(TileCtx<D>& c, const bf16x8 (&pb)[4], 
 //   V: within a 16-lane group, lane j points at row j/4, columns 4 (j%4)..+3 of a 4 x 16
 //      patch of the transpose read and lane i receives column i; lane half h covers rows +4h.
 template <int D>
-__device__ __forceinline__ void k_addresses(const char* lds_k, int n, int h, unsigned (&kaddr)[D / 16])
+__device__ __forceinline__ void k_addresses(const char* lds_k, int n, int h, TileCtx<D>& c)
 {
     typedef Geo<D> G;
-    const unsigned kbase = (unsigned)(size_t)LDS_PTR(const char, lds_k) + n * G::ROW_BYTES;
-    const int kx = h ^ G::swz_k(n);                        // chunk (2t+h) ^ swz == (2t) ^ kx
-#pragma unroll
-    for (int t = 0; t < D / 16; ++t) kaddr[t] = kbase + (((2 * t) ^ kx) << 4);
+    c.kbase = (unsigned)(size_t)LDS_PTR(const char, lds_k) + n * G::ROW_BYTES;
+    c.kxor = (unsigned)(h ^ G::swz_k(n)) << 4;
 }
 
 template <int D>
@@ -408,7 +422,7 @@ __device__ __forceinline__ void compute_tile(const char* lds_k, const char* lds_
 {
     typedef TileItems<D> TI;
     TileCtx<D> ctx;
-    k_addresses<D>(lds_k, n, h, ctx.kaddr);
+    k_addresses<D>(lds_k, n, h, ctx);
     v_addresses<D>(lds_v, h, tr_row, tr_col, ctx.vaddr);
     bf16x8 pb[4];
     f32x16 st[2];
@@ -717,7 +731,7 @@ __global__ __launch_bounds__(512, 2) void attn_dense_pp_kernel(const AttnParams 
     TileCtx<D> ctx;
     bf16x8 pb[4];
     f32x16 st[2];
-    k_addresses<D>(stage_k(0), n, h, ctx.kaddr);
+    k_addresses<D>(stage_k(0), n, h, ctx);
     items_prefetch<D, TI::NPV, TI::NI>(ctx);
     items_run<D, TI::NPV, TI::NI>(ctx, pb, qf, acc, st);   // S_0
     mask_tail(st, 0, kv_len, h);
@@ -747,11 +761,254 @@ __global__ __launch_bounds__(512, 2) void attn_dense_pp_kernel(const AttnParams 
             }
             // PV(j) then QK(j+1) as one stream.  For the last tile the QK half re-reads a
             // landed stage and its result is never used.
-            k_addresses<D>(stage_k((j + 1 < T) ? ((s + 1) & 3) : s), n, h, ctx.kaddr);
+            k_addresses<D>(stage_k((j + 1 < T) ? ((s + 1) & 3) : s), n, h, ctx);
             items_run<D, 0, TI::NI>(ctx, pb, qf, acc, st);
             mask_tail(st, (j + 1) * KT, kv_len, h);
             __builtin_amdgcn_s_setprio(0);
         }
+    }
+    if (group == 0) __syncthreads();              // same number of barriers for every wavefront
+
+    write_output<D>(O, acc, sm.l, qrow, qvalid, p.N, h);
+}
+
+// ---------------------------------------------------------------------------
+// Dense path, balanced phases.  Same two-group anti-phase scheme as attn_dense_pp_kernel,
+// but the work of a tile is cut so that BOTH phases carry half of the MFMAs:
+//   P1(j)  O^T += V_{j-1}^T P_{j-1}^T (16 MFMAs at D=128)  interleaved with  the softmax of
+//          S_j: row max, reference update, exp / sum / bf16 conversion -> P_j
+//   P2(j)  S_{j+1} = K_{j+1} Q^T (16 MFMAs), the tile copies
+// Between two barriers one group runs a P1 and the other a P2, so both wavefronts of a
+// SIMD feed the matrix pipe all the time and the vector work rides along with it.
+// When the reference max moves, P_j already uses the new reference while O still holds
+// tiles < j in the old one: O (including the P1(j) products, all in the old reference) is
+// rescaled at the end of P1(j), before P_j is ever multiplied in.
+// Slots (intervals between barriers): group 0 runs P1(j) in slot 2j+1 and P2(j) in slot
+// 2j+2, group 1 one slot later; a last P1(T) does the products of the last tile.
+// Copies: event E(j) = {K_{j+4}, V_{j+2}}, issued in P2(j) into the stages of K_j (last read
+// in slot 2j+1) and V_{j-2} (slot 2j).  Before every barrier a wavefront waits for all of
+// its copies except its newest event, so K_{j+1} and V_{j-1} (event E(j-3)) are complete
+// from slot 2j on: in time for the fragment prefetch at the end of the preceding phase.
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ float tile_max_step(float mx, const f32x16 (&st)[2], int i)
+{
+    return fmaxf(fmaxf(mx, st[0][i]), st[1][i]);
+}
+
+// exp / sum / conversion of score values 2*CH and 2*CH+1 (flattened in MFMA-operand order:
+// value v -> pb[v / 8][v % 8] = st[(v / 8) >> 1][8 * ((v / 8) & 1) + v % 8])
+template <int CH>
+__device__ __forceinline__ void softmax_chunk(const f32x16 (&st)[2], float c, float mc, float& rs0, float& rs1,
+                                              bf16x8 (&pb)[4])
+{
+    constexpr int g = CH / 4, k = 2 * (CH % 4), rb = g >> 1, off = 8 * (g & 1) + k;
+    const float e0 = __builtin_amdgcn_exp2f(__builtin_fmaf(st[rb][off], c, -mc));
+    const float e1 = __builtin_amdgcn_exp2f(__builtin_fmaf(st[rb][off + 1], c, -mc));
+    rs0 += e0;
+    rs1 += e1;
+    pb[g][k] = (__bf16)e0;
+    pb[g][k + 1] = (__bf16)e1;
+    // values computed from registers only may be moved anywhere; tying the sums to an empty
+    // volatile statement keeps this chunk between the LDS requests it was written between
+    asm volatile("" : "+v"(rs0), "+v"(rs1));
+}
+
+template <int CH, int END>
+__device__ __forceinline__ void softmax_chunks(const f32x16 (&st)[2], float c, float mc, float& rs0, float& rs1,
+                                               bf16x8 (&pb)[4])
+{
+    if constexpr (CH < END) {
+        softmax_chunk<CH>(st, c, mc, rs0, rs1, pb);
+        softmax_chunks<CH + 1, END>(st, c, mc, rs0, rs1, pb);
+    }
+}
+
+struct P1State {
+    float mx;        // running row max of the tile being exponentiated
+    float mc;        // reference max * c
+    float alpha;     // factor the accumulators still have to be multiplied by (1 = none)
+    float rs0, rs1;  // partial row sums
+};
+
+// The VALU work attached to PV item I (of NPV): the first quarter of the items carry the
+// max steps, then the reference is updated, then half of the items carry the exp chunks.
+template <int D, int I>
+__device__ __forceinline__ void p1_valu(const f32x16 (&st)[2], SoftmaxState& sm, P1State& ps, float c, float tau,
+                                        bf16x8 (&pb_new)[4])
+{
+    constexpr int NPV = TileItems<D>::NPV;
+    constexpr int MI = NPV / 4, NE = NPV / 2;
+    constexpr int MS = 16 / MI, CS = 16 / NE;
+    if constexpr (I < MI) {
+#pragma unroll
+        for (int m = 0; m < MS; ++m) ps.mx = tile_max_step(ps.mx, st, I * MS + m);
+    }
+    if constexpr (I == MI - 1) {
+        auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(ps.mx), __float_as_uint(ps.mx), false, false);
+        const float mx = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
+        // Lazy rescale: keep the old reference while the new max exceeds it by at most tau
+        // (probabilities then stay below 2^8); any reference gives the same quotient.
+        ps.alpha = 1.0f;
+        if (__builtin_amdgcn_ballot_w64(mx > sm.m + tau) != 0ull) {
+            const float m_new = fmaxf(sm.m, mx);          // finite: every visited tile has a valid key
+            ps.alpha = __builtin_amdgcn_exp2f((sm.m - m_new) * c);
+            sm.m = m_new;
+            sm.l *= ps.alpha;
+        }
+        ps.mc = sm.m * c;
+    }
+    if constexpr (I >= MI && I < MI + NE)
+        softmax_chunks<(I - MI) * CS, (I - MI + 1) * CS>(st, c, ps.mc, ps.rs0, ps.rs1, pb_new);
+}
+
+// P1: PV items of tile j-1 interleaved with the softmax of tile j.
+template <int D, int I = 0>
+__device__ __forceinline__ void p1_steps(TileCtx<D>& ctx, const bf16x8 (&qf)[D / 16], const bf16x8 (&pb_old)[4],
+                                         f32x16 (&acc)[D / 32], f32x16 (&st)[2], SoftmaxState& sm, P1State& ps,
+                                         float c, float tau, bf16x8 (&pb_new)[4])
+{
+    typedef TileItems<D> TI;
+    if constexpr (I < TI::NPV) {
+        if constexpr (I + TI::PD < TI::NPV) item_request<D, I + TI::PD>(ctx);
+        item_wait<D, I, TI::NPV>(ctx);
+        item_mfma<D, I>(ctx, pb_old, qf, acc, st);
+        p1_valu<D, I>(st, sm, ps, c, tau, pb_new);
+        __builtin_amdgcn_sched_barrier(0);                 // keep the interleave as written
+        p1_steps<D, I + 1>(ctx, qf, pb_old, acc, st, sm, ps, c, tau, pb_new);
+    }
+}
+
+template <int D>
+__global__ __launch_bounds__(512, 2) void attn_dense_bp_kernel(const AttnParams p)
+{
+    typedef Geo<D> G;
+    typedef TileItems<D> TI;
+    constexpr int NW = 8, QT = 256, KS = D / 16, DB = D / 32;
+    constexpr int LPT = 2 * G::LOADS / NW;        // copy instructions per wavefront per event
+
+    __shared__ __attribute__((aligned(1024))) char lds[8 * G::TILE_BYTES];     // K stages 0..3, V stages 4..7
+    auto k_stage = [&](int t) -> char* { return lds + (t & 3) * G::TILE_BYTES; };
+    auto v_stage = [&](int t) -> char* { return lds + (4 + (t & 3)) * G::TILE_BYTES; };
+
+    const int wg = blockIdx.x;
+    const int item = (wg % XCDS) * p.chunk + wg / XCDS;     // XCD-aware: see attn_kernel
+    if (item >= p.items) return;
+    const int bh = item / p.nq;
+    const int qi = item % p.nq;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int group = wave >> 2;
+    const int n = lane & 31;
+    const int h = lane >> 5;
+    const int kv_len = p.kv_len;
+
+    const size_t base = (size_t)bh * p.N * D;
+    const __bf16* __restrict__ Q = p.q + base;
+    const __bf16* __restrict__ K = p.k + base;
+    const __bf16* __restrict__ V = p.v + base;
+    __bf16* __restrict__ O = p.o + base;
+
+    const int T = (kv_len + KT - 1) / KT;         // >= 1
+
+#pragma unroll
+    for (int t = 0; t < 4; ++t)
+        if (t < T) issue_tile<D, NW, false>(K, t * KT, kv_len, k_stage(t), wave, lane);
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+        if (t < T) issue_tile<D, NW, true>(V, t * KT, kv_len, v_stage(t), wave, lane);
+
+    const int qrow = qi * QT + wave * 32 + n;
+    const bool qvalid = qrow < kv_len;
+    bf16x8 qf[KS];
+    load_q<D>(Q, qrow, qvalid, h, qf);
+
+    f32x16 acc[DB];
+#pragma unroll
+    for (int i = 0; i < DB; ++i)
+#pragma unroll
+        for (int j = 0; j < 16; ++j) acc[i][j] = 0.f;
+    SoftmaxState sm;
+    sm.m = -INFINITY;
+    sm.l = 0.f;
+    const float tau = 8.0f / p.c;
+    const int tr_row = (lane & 15) >> 2;
+    const int tr_col = ((lane & 3) << 2) + (((lane >> 4) & 1) << 4);
+
+    wait_vmcnt<0>();                              // Q fragments and the first tiles
+    __syncthreads();
+    if (group == 1) __syncthreads();              // group 1 runs one barrier behind
+
+    TileCtx<D> ctx;
+    bf16x8 pba[4], pbb[4];
+    f32x16 st[2];
+    // S_0
+    k_addresses<D>(k_stage(0), n, h, ctx);
+    items_prefetch<D, TI::NPV, TI::NI>(ctx);
+    items_run<D, TI::NPV, TI::NI>(ctx, pba, qf, acc, st);
+    mask_tail(st, 0, kv_len, h);
+
+    auto slot_barrier = [&](int j) {              // all copies but the newest event E(j-1)
+        if (j + 3 < T) wait_vmcnt<LPT>();
+        else wait_vmcnt<0>();
+        phase_barrier();
+    };
+    auto phase1_tail = [&](P1State& ps) {         // row sums, deferred rescale of O
+        sm.l += ps.rs0 + ps.rs1;
+        if (__builtin_amdgcn_ballot_w64(ps.alpha != 1.0f) != 0ull) {
+#pragma unroll
+            for (int i = 0; i < DB; ++i)
+#pragma unroll
+                for (int jj = 0; jj < 16; ++jj) acc[i][jj] *= ps.alpha;
+        }
+    };
+    // Iteration j = 0 .. T.  pb_old = P_{j-1} (consumed), pb_new = P_j (produced).  One code
+    // path for all j: at j = 0, P_{-1} = 0 is multiplied into tile 0's V (adds nothing); at
+    // j = T the "scores" are -inf, which leaves the softmax state untouched.
+    auto tile_iter = [&](int j, bf16x8 (&pb_old)[4], bf16x8 (&pb_new)[4]) {
+        slot_barrier(j);
+        // ---- P1(j): PV(j-1) with softmax(S_j)
+        if (j == T) {
+            asm volatile("");                     // a real branch, not 32 selects per tile
+#pragma unroll
+            for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) st[rb][i] = -INFINITY;
+        }
+        P1State ps;
+        ps.mx = st[0][0]; ps.mc = 0.f; ps.alpha = 1.0f; ps.rs0 = 0.f; ps.rs1 = 0.f;
+        p1_steps<D>(ctx, qf, pb_old, acc, st, sm, ps, p.c, tau, pb_new);
+        phase1_tail(ps);
+        pin_in_phase(pb_new, sm.l);
+        if (j + 1 < T) {
+            k_addresses<D>(k_stage(j + 1), n, h, ctx);
+            items_prefetch<D, TI::NPV, TI::NI>(ctx);  // first K_{j+1} fragments of P2(j)
+        }
+        if (j < T) {
+            slot_barrier(j);
+            // ---- P2(j): copies of E(j), S_{j+1}
+            if (j + 4 < T) issue_tile<D, NW, false>(K, (j + 4) * KT, kv_len, k_stage(j + 4), wave, lane);
+            if (j + 2 < T) issue_tile<D, NW, true>(V, (j + 2) * KT, kv_len, v_stage(j + 2), wave, lane);
+            if (j + 1 < T) {
+                items_run<D, TI::NPV, TI::NI>(ctx, pb_new, qf, acc, st);
+                mask_tail(st, (j + 1) * KT, kv_len, h);
+            }
+            v_addresses<D>(v_stage(j), h, tr_row, tr_col, ctx.vaddr);
+            items_prefetch<D, 0, TI::NPV>(ctx);   // first V_j^T fragments of P1(j+1)
+        }
+    };
+
+#pragma unroll
+    for (int g = 0; g < 4; ++g)
+#pragma unroll
+        for (int i = 0; i < 8; ++i) pbb[g][i] = (__bf16)0.f;
+    v_addresses<D>(v_stage(0), h, tr_row, tr_col, ctx.vaddr);
+    items_prefetch<D, 0, TI::NPV>(ctx);           // P1(0) multiplies zeros into V_0 (landed)
+    for (int j = 0; j <= T; j += 2) {
+        tile_iter(j, pbb, pba);
+        if (j + 1 > T) break;
+        tile_iter(j + 1, pba, pbb);
     }
     if (group == 0) __syncthreads();              // same number of barriers for every wavefront
 
@@ -886,7 +1143,7 @@ __global__ __launch_bounds__(128 * WPG, 2) void attn_sparse_pp_kernel(const Attn
     int t = group;                                // this group's tiles: group, group + 2, ...
     if (t < T) {                                  // slot t: S_t on its own
         slot_begin();
-        k_addresses<D>(k_stage(t), n, h, ctx.kaddr);
+        k_addresses<D>(k_stage(t), n, h, ctx);
         items_prefetch<D, TI::NPV, TI::NI>(ctx);
         items_run<D, TI::NPV, TI::NI>(ctx, pb, qf, acc, st);
         mask_tail(st, kq[0], kv_len, h);
@@ -904,7 +1161,7 @@ __global__ __launch_bounds__(128 * WPG, 2) void attn_sparse_pp_kernel(const Attn
         __builtin_amdgcn_s_setprio(3);
         slot_begin();
         // (without a tile t+2 the QK half re-reads K_t, which is landed, and is dropped)
-        k_addresses<D>(k_stage((t + 2 < T) ? t + 2 : t), n, h, ctx.kaddr);
+        k_addresses<D>(k_stage((t + 2 < T) ? t + 2 : t), n, h, ctx);
         items_run<D, 0, TI::NI>(ctx, pb, qf, acc, st);
         mask_tail(st, kq[0], kv_len, h);
         __builtin_amdgcn_s_setprio(0);
@@ -1021,7 +1278,14 @@ int rapid_attn_dense(const void* q, const void* k, const void* v, void* o,
     p.block = 0; p.nb = 0; p.sub_shift = 0;
     p.c = scale * LOG2E;
     hipStream_t s = (hipStream_t)stream;
-#if DENSE_PINGPONG
+#if DENSE_PINGPONG == 2
+    {
+        const int grid = p.chunk * XCDS;
+        if (D == 64) hipLaunchKernelGGL((attn_dense_bp_kernel<64>), dim3(grid), dim3(512), 0, s, p);
+        else hipLaunchKernelGGL((attn_dense_bp_kernel<128>), dim3(grid), dim3(512), 0, s, p);
+        return hipGetLastError() == hipSuccess ? RAPID_OK : RAPID_ERR_DEVICE;
+    }
+#elif DENSE_PINGPONG == 1
     {
         const int grid = p.chunk * XCDS;
         if (D == 64) hipLaunchKernelGGL((attn_dense_pp_kernel<64>), dim3(grid), dim3(512), 0, s, p);
