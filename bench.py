@@ -32,6 +32,19 @@ if ROOT not in sys.path:
 PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA peak (published, no sparsity)
 
 
+def measured_traffic(workload):
+    """HBM bytes per launch of the dense kernel, from the committed rocprofv3 --pmc summary
+    (FETCH_SIZE and WRITE_SIZE runs scaled by a plain copy); None if there is none."""
+    path = os.path.join(ROOT, "profiles", f"attn_dense_pp_kernel_{workload}.txt")
+    try:
+        for line in open(path):
+            if line.startswith("TRAFFIC_BYTES_PER_LAUNCH="):
+                return int(line.split("=", 1)[1])
+    except OSError:
+        pass
+    return None
+
+
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -41,6 +54,9 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-sparse", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a plain device copy of the Q tensor (known size) so that HBM "
+                         "counters collected around this process can be scaled")
     return ap.parse_args()
 
 
@@ -107,11 +123,18 @@ def main():
                                f"dense (action 0), one layer's attention per step",
                    "flops_per_step": dense_flops, "entry": "rapid_attn_dense"},
         "pct_of_bf16_mfma_peak": round(100.0 * value / PEAK_BF16_TFLOPS, 2),
-        "roofline": {"bound": "mfma", "kernel": f"attn_kernel<D={w.D}>", "achieved": round(achieved, 2),
+        "roofline": {"bound": "mfma", "kernel": f"attn_dense_pp_kernel<{w.D}>", "achieved": round(achieved, 2),
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                     "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": None,
+                     "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": measured_traffic(w.name),
+                     "algorithmic_bytes": 4 * dq.numel() * 2,
                      "launch_ms_mean": round(ev_mean, 5), "launch_ms_min": round(ev_min, 5)},
     }
+
+    if args.calibrate_copy:                        # 2 x Q bytes of HBM traffic, for counter calibration
+        for _ in range(5):
+            do.copy_(dq)
+        torch.cuda.synchronize()
+        out["calibration_copy_bytes"] = 2 * dq.numel() * 2
 
     # ---- block-sparse entry point at the workload's densities (compaction included)
     if not args.no_sparse:

@@ -5,22 +5,29 @@
 // per layer and per head).  The pruned map is given as a block mask; pruned tiles
 // are never read.
 //
-// Kernel shape.  One workgroup owns one query tile of 32*NW rows (NW wavefronts,
-// 32 query rows each) of one (sample, head) and walks over 64-key tiles:
+// Building blocks (a wavefront always owns 32 queries and walks over 64-key tiles):
 //   S^T = K Q^T    v_mfma_f32_32x32x16_bf16, A = K tile rows from LDS (128-bit
-//                  reads), B = the wave's Q rows held in registers for the whole
-//                  kernel.  Computing the TRANSPOSED score tile puts one query
-//                  per lane: the running max / sum are per-lane scalars, the row
-//                  reductions are in-register plus ONE cross-half exchange
+//                  reads), B = the wavefront's Q rows held in registers for the
+//                  whole kernel.  Computing the TRANSPOSED score tile puts one
+//                  query per lane: the running max / sum are per-lane scalars, the
+//                  row reductions are in-register plus ONE cross-half exchange
 //                  (v_permlane32_swap), and the fp32 accumulator registers of a
 //                  lane are, after conversion to bf16, exactly the B operand of
 //                  the next product -- P never touches LDS.
 //   O^T += V^T P^T same MFMA; A = V^T fragments fetched straight out of the
 //                  row-major V tile with the LDS transpose read
 //                  (ds_read_b64_tr_b16), B = P^T from the registers above.
-// The contraction index of the second product is a dummy, so its key order
-// inside a 16-key step is whatever the accumulator layout yields (keys
-// 4h+r and 8+4h+r for lane half h); the V^T fragments are fetched in that order.
+//                  The contraction index is a dummy, so the key order inside a
+//                  16-key step is whatever the accumulator layout yields (keys
+//                  4h+r and 8+4h+r for lane half h); V^T is fetched in that order.
+//   tiles          global -> LDS directly (global_load_lds_dwordx4), chunk-swizzled,
+//                  several tiles ahead of their use.
+// Kernels:
+//   attn_dense_pp_kernel   256 queries per workgroup, 8 wavefronts in two groups that
+//                          alternate a softmax phase and an MFMA phase in anti-phase
+//   attn_sparse_pp_kernel  one mask query-block per workgroup; the kept-tile list is
+//                          split between the two groups and merged at the end
+//   compact_mask_kernel, plan_kernel   kept-tile lists and launch order of the sparse path
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -38,15 +45,7 @@ typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 
 constexpr int KT = 64;          // keys per LDS tile
 constexpr int XCDS = 8;         // L2 domains the dispatcher deals workgroups over
-#ifndef DENSE_QT
-#define DENSE_QT 256            // query rows per workgroup on the dense path
-#endif
-#ifndef DENSE_NS
-#define DENSE_NS 3              // LDS stages on the dense path
-#endif
-#ifndef DENSE_PINGPONG
-#define DENSE_PINGPONG 1        // dense path: 1 = softmax/MFMA phases in anti-phase, 2 = balanced phases, 0 = free-running
-#endif
+constexpr int DENSE_QT = 256;    // query rows per workgroup on the dense path
 constexpr float LOG2E = 1.44269504088896340736f;
 
 #define LDS_PTR(T, p) ((__attribute__((address_space(3))) T*)(p))
@@ -414,26 +413,6 @@ __device__ __forceinline__ void softmax_tile(const f32x16 (&st)[2], f32x16 (&acc
     st_.l += rs0 + rs1;
 }
 
-// One 64-key tile in sequence: S^T = K Q^T, online softmax, O^T += V^T P^T.
-template <int D>
-__device__ __forceinline__ void compute_tile(const char* lds_k, const char* lds_v, const bf16x8 (&qf)[D / 16],
-                                             f32x16 (&acc)[D / 32], SoftmaxState& st_, int key0, int kv_len,
-                                             float c, float tau, int n, int h, int tr_row, int tr_col)
-{
-    typedef TileItems<D> TI;
-    TileCtx<D> ctx;
-    k_addresses<D>(lds_k, n, h, ctx);
-    v_addresses<D>(lds_v, h, tr_row, tr_col, ctx.vaddr);
-    bf16x8 pb[4];
-    f32x16 st[2];
-    items_prefetch<D, TI::NPV, TI::NI>(ctx);
-    items_run<D, TI::NPV, TI::NI>(ctx, pb, qf, acc, st);
-    mask_tail(st, key0, kv_len, h);
-    items_prefetch<D, 0, TI::NPV>(ctx);                    // first V^T fragments: consumed after the softmax
-    softmax_tile<D>(st, acc, st_, c, tau, pb);
-    items_run<D, 0, TI::NPV>(ctx, pb, qf, acc, st);
-}
-
 // Epilogue: O = acc / l as bf16.  Register 4j+r of block db holds d = 32 db + 8 j + 4 h + r
 // of this lane's query; rows at or beyond kv_len and rows without any kept key become 0.
 template <int D>
@@ -483,143 +462,6 @@ __device__ __forceinline__ void wait_vmcnt()
     __builtin_amdgcn_s_waitcnt(0x0F70 | (VM & 15) | ((VM >> 4) << 14));
 }
 
-// NW wavefronts x 32 queries; NS LDS stages (tile t lives in stage t % NS, its copy is
-// issued NS-1 tiles ahead); WPE = wavefronts per SIMD the register budget is held to.
-template <int D, int NW, int NS, int WPE>
-__global__ __launch_bounds__(64 * NW, WPE) void attn_kernel(const AttnParams p)
-{
-    typedef Geo<D> G;
-    constexpr int QT = 32 * NW;
-    constexpr int KS = D / 16;                    // k-steps of the QK^T product
-    constexpr int DB = D / 32;                    // 32-row blocks of O^T
-    constexpr int LPT = 2 * G::LOADS / NW;        // copy instructions per wavefront per tile (K + V)
-
-    // K and V tile rings.  Every stage is its own array (unused ones are dropped) and is
-    // selected with compile-time constants only: the compiler then knows that the stage
-    // being filled is not the stage being read and adds no wait between the two.
-    static_assert(NS >= 2 && NS <= 4, "2 to 4 stages");
-    __shared__ __attribute__((aligned(1024))) char lds_k0[G::TILE_BYTES];
-    __shared__ __attribute__((aligned(1024))) char lds_k1[G::TILE_BYTES];
-    __shared__ __attribute__((aligned(1024))) char lds_k2[G::TILE_BYTES];
-    __shared__ __attribute__((aligned(1024))) char lds_k3[G::TILE_BYTES];
-    __shared__ __attribute__((aligned(1024))) char lds_v0[G::TILE_BYTES];
-    __shared__ __attribute__((aligned(1024))) char lds_v1[G::TILE_BYTES];
-    __shared__ __attribute__((aligned(1024))) char lds_v2[G::TILE_BYTES];
-    __shared__ __attribute__((aligned(1024))) char lds_v3[G::TILE_BYTES];
-    auto stage_k = [&](int st) -> char* { return st == 0 ? lds_k0 : st == 1 ? lds_k1 : st == 2 ? lds_k2 : lds_k3; };
-    auto stage_v = [&](int st) -> char* { return st == 0 ? lds_v0 : st == 1 ? lds_v1 : st == 2 ? lds_v2 : lds_v3; };
-
-    // XCD-aware work mapping: the dispatcher deals consecutive workgroup ids
-    // round-robin over the 8 XCDs, so give each XCD a contiguous run of items
-    // (query tiles of the same head share K/V in that XCD's L2).
-    const int wg = blockIdx.x;
-    int item = (wg % XCDS) * p.chunk + wg / XCDS;
-    if (item >= p.items) return;
-    const int bh = item / p.nq;
-    const int qi = item % p.nq;
-
-    const int tid = threadIdx.x;
-    const int lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int n = lane & 31;                      // query within the wave / MFMA column
-    const int h = lane >> 5;                      // lane half
-    const int kv_len = p.kv_len;
-
-    const size_t base = (size_t)bh * p.N * D;
-    const __bf16* __restrict__ Q = p.q + base;
-    const __bf16* __restrict__ K = p.k + base;
-    const __bf16* __restrict__ V = p.v + base;
-    __bf16* __restrict__ O = p.o + base;
-
-    // key tiles to visit: tile t -> first key
-    // (the kept-tile list is read through the constant address space so that the reads
-    // are scalar loads: they must not share a counter with the tile copies in flight)
-    typedef const __attribute__((address_space(4))) int32_t* cptr_t;
-    const int ss = p.sub_shift;                   // log2(64-key tiles per mask block)
-    const bool sparse = p.counts != nullptr;
-    cptr_t list = (cptr_t)(p.index + (size_t)item * p.nb);
-    int T;
-    if (sparse) {
-        const int n_blocks = ((cptr_t)p.counts)[item];
-        T = n_blocks << ss;
-        if (n_blocks > 0 && (((list[n_blocks - 1] + 1) << ss) - 1) * KT >= kv_len) T -= 1;
-    } else {
-        T = (kv_len + KT - 1) / KT;
-    }
-    auto tile_key0 = [&](int t) -> int {
-        if (!sparse) return t * KT;
-        return ((list[t >> ss] << ss) + (t & ((1 << ss) - 1))) * KT;
-    };
-
-    // prologue: copies of the first NS-1 tiles; key_ring[s] = first key of the tile in stage s
-    int key_ring[NS];
-#pragma unroll
-    for (int st = 0; st < NS; ++st) key_ring[st] = 0;
-#pragma unroll
-    for (int st = 0; st < NS - 1; ++st) {
-        if (st < T) {
-            key_ring[st] = tile_key0(st);
-            issue_tile<D, NW, false>(K, key_ring[st], kv_len, stage_k(st), wave, lane);
-            issue_tile<D, NW, true>(V, key_ring[st], kv_len, stage_v(st), wave, lane);
-        }
-    }
-    int key_pref = (NS - 1 < T) ? tile_key0(NS - 1) : 0;   // first key of the next tile to issue
-
-    const int qrow = qi * QT + wave * 32 + n;     // this lane's query row
-    const bool qvalid = qrow < kv_len;            // kv_len <= N
-
-    bf16x8 qf[KS];
-    load_q<D>(Q, qrow, qvalid, h, qf);
-
-    f32x16 acc[DB];
-#pragma unroll
-    for (int i = 0; i < DB; ++i)
-#pragma unroll
-        for (int j = 0; j < 16; ++j) acc[i][j] = 0.f;
-    SoftmaxState sm;
-    sm.m = -INFINITY;
-    sm.l = 0.f;
-    const float tau = 8.0f / p.c;                 // 2^8 head-room on the probabilities
-
-    // per-lane offsets of the transpose read: within a 16-lane group, lane j points
-    // at row j/4, columns 4*(j%4)..+3 of a 4 x 16 patch; lane i receives column i.
-    const int tr_row = (lane & 15) >> 2;
-    const int tr_col = ((lane & 3) << 2) + (((lane >> 4) & 1) << 4);
-
-    // The Q fragments must have arrived before the loop: a wait for them inside the loop
-    // would also wait for every tile copy in flight.
-    wait_vmcnt<0>();
-
-    // Pipeline: tile t is computed out of stage t % NS while the copies of tiles
-    // t+1 .. t+NS-1 are in flight.  One barrier per tile: after it, tile t is visible to
-    // all wavefronts and all of them have finished reading the stage of tile t-1, which
-    // is the stage the copy of tile t+NS-1 is then issued into.
-    for (int t0 = 0; t0 < T; t0 += NS) {
-#pragma unroll
-        for (int st = 0; st < NS; ++st) {
-            const int t = t0 + st;
-            if (t >= T) break;
-            // my copies of tile t have landed once at most the copies of the tiles issued
-            // after it are outstanding (vector-memory operations complete in order)
-            if (NS >= 3 && t + NS - 2 < T) wait_vmcnt<(NS - 2) * LPT>();
-            else if (NS >= 4 && t + NS - 3 < T) wait_vmcnt<(NS >= 4 ? (NS - 3) * LPT : 0)>();
-            else if (NS >= 4 && t + 1 < T) wait_vmcnt<(NS >= 4 ? LPT : 0)>();
-            else wait_vmcnt<0>();
-            __syncthreads();
-            const int nst = (st + NS - 1) % NS;    // a constant once unrolled
-            if (t + NS - 1 < T) {
-                key_ring[nst] = key_pref;
-                issue_tile<D, NW, false>(K, key_pref, kv_len, stage_k(nst), wave, lane);
-                issue_tile<D, NW, true>(V, key_pref, kv_len, stage_v(nst), wave, lane);
-                if (t + NS < T) key_pref = tile_key0(t + NS);
-            }
-            compute_tile<D>(stage_k(st), stage_v(st), qf, acc, sm, key_ring[st], kv_len, p.c, tau, n, h, tr_row, tr_col);
-        }
-    }
-
-    write_output<D>(O, acc, sm.l, qrow, qvalid, p.N, h);
-}
-
 // Values computed from registers only carry no ordering against a barrier; an empty volatile
 // assembly statement that "modifies" them makes them complete before whatever follows it.
 __device__ __forceinline__ void pin_in_phase(bf16x8 (&pb)[4], float& l)
@@ -662,22 +504,21 @@ template <int D>
 __global__ __launch_bounds__(512, 2) void attn_dense_pp_kernel(const AttnParams p)
 {
     typedef Geo<D> G;
-    constexpr int NW = 8, QT = 256, KS = D / 16, DB = D / 32;
+    typedef TileItems<D> TI;
+    constexpr int NW = 8, QT = DENSE_QT, KS = D / 16, DB = D / 32;
     constexpr int LPT = 2 * G::LOADS / NW;        // copy instructions per wavefront per tile (K + V)
 
-    __shared__ __attribute__((aligned(1024))) char lds_k0[G::TILE_BYTES];
-    __shared__ __attribute__((aligned(1024))) char lds_k1[G::TILE_BYTES];
-    __shared__ __attribute__((aligned(1024))) char lds_k2[G::TILE_BYTES];
-    __shared__ __attribute__((aligned(1024))) char lds_k3[G::TILE_BYTES];
-    __shared__ __attribute__((aligned(1024))) char lds_v0[G::TILE_BYTES];
-    __shared__ __attribute__((aligned(1024))) char lds_v1[G::TILE_BYTES];
-    __shared__ __attribute__((aligned(1024))) char lds_v2[G::TILE_BYTES];
-    __shared__ __attribute__((aligned(1024))) char lds_v3[G::TILE_BYTES];
-    auto stage_k = [&](int st) -> char* { return st == 0 ? lds_k0 : st == 1 ? lds_k1 : st == 2 ? lds_k2 : lds_k3; };
-    auto stage_v = [&](int st) -> char* { return st == 0 ? lds_v0 : st == 1 ? lds_v1 : st == 2 ? lds_v2 : lds_v3; };
+    // All LDS traffic of the loop is explicit assembly, so the stages are plain runtime
+    // offsets into one array: K stages 0..3, V stages 4..7; tile t lives in stage t % 4.
+    __shared__ __attribute__((aligned(1024))) char lds[8 * G::TILE_BYTES];
+    auto k_stage = [&](int t) -> char* { return lds + (t & 3) * G::TILE_BYTES; };
+    auto v_stage = [&](int t) -> char* { return lds + (4 + (t & 3)) * G::TILE_BYTES; };
 
+    // XCD-aware work mapping: the dispatcher deals consecutive workgroup ids round-robin
+    // over the 8 XCDs, so give each XCD a contiguous run of items (query tiles of the same
+    // head then share K/V in that XCD's L2).
     const int wg = blockIdx.x;
-    const int item = (wg % XCDS) * p.chunk + wg / XCDS;     // XCD-aware: see attn_kernel
+    const int item = (wg % XCDS) * p.chunk + wg / XCDS;
     if (item >= p.items) return;
     const int bh = item / p.nq;
     const int qi = item % p.nq;
@@ -686,8 +527,8 @@ __global__ __launch_bounds__(512, 2) void attn_dense_pp_kernel(const AttnParams 
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int group = wave >> 2;
-    const int n = lane & 31;
-    const int h = lane >> 5;
+    const int n = lane & 31;                      // query within the wavefront / MFMA column
+    const int h = lane >> 5;                      // lane half
     const int kv_len = p.kv_len;
 
     const size_t base = (size_t)bh * p.N * D;
@@ -699,15 +540,15 @@ __global__ __launch_bounds__(512, 2) void attn_dense_pp_kernel(const AttnParams 
     const int T = (kv_len + KT - 1) / KT;         // >= 1
 
 #pragma unroll
-    for (int st = 0; st < 3; ++st) {
-        if (st < T) {
-            issue_tile<D, NW, false>(K, st * KT, kv_len, stage_k(st), wave, lane);
-            issue_tile<D, NW, true>(V, st * KT, kv_len, stage_v(st), wave, lane);
+    for (int t = 0; t < 3; ++t) {
+        if (t < T) {
+            issue_tile<D, NW, false>(K, t * KT, kv_len, k_stage(t), wave, lane);
+            issue_tile<D, NW, true>(V, t * KT, kv_len, v_stage(t), wave, lane);
         }
     }
 
-    const int qrow = qi * QT + wave * 32 + n;
-    const bool qvalid = qrow < kv_len;
+    const int qrow = qi * QT + wave * 32 + n;     // this lane's query row
+    const bool qvalid = qrow < kv_len;            // kv_len <= N
     bf16x8 qf[KS];
     load_q<D>(Q, qrow, qvalid, h, qf);
 
@@ -719,296 +560,49 @@ __global__ __launch_bounds__(512, 2) void attn_dense_pp_kernel(const AttnParams 
     SoftmaxState sm;
     sm.m = -INFINITY;
     sm.l = 0.f;
-    const float tau = 8.0f / p.c;
+    const float tau = 8.0f / p.c;                 // 2^8 head-room on the probabilities
     const int tr_row = (lane & 15) >> 2;
     const int tr_col = ((lane & 3) << 2) + (((lane >> 4) & 1) << 4);
 
-    wait_vmcnt<0>();                              // Q fragments and the first tiles
+    // The Q fragments and the first tiles must have arrived before the loop (a wait for
+    // the Q loads inside the loop would also wait for every tile copy in flight).
+    wait_vmcnt<0>();
     __syncthreads();
     if (group == 1) __syncthreads();              // group 1 runs one barrier behind
 
-    typedef TileItems<D> TI;
     TileCtx<D> ctx;
     bf16x8 pb[4];
     f32x16 st[2];
-    k_addresses<D>(stage_k(0), n, h, ctx);
+    k_addresses<D>(k_stage(0), n, h, ctx);
     items_prefetch<D, TI::NPV, TI::NI>(ctx);
     items_run<D, TI::NPV, TI::NI>(ctx, pb, qf, acc, st);   // S_0
     mask_tail(st, 0, kv_len, h);
 
-    for (int j0 = 0; j0 < T; j0 += 4) {
-#pragma unroll
-        for (int s = 0; s < 4; ++s) {
-            const int j = j0 + s;
-            if (j >= T) break;
-            // my share of tile j+1 (outstanding: tiles j+1 and j+2, completing in order)
-            if (j + 2 < T) wait_vmcnt<LPT>();
-            else wait_vmcnt<0>();
-            phase_barrier();
-
-            // ---- B(j)
-            v_addresses<D>(stage_v(s), h, tr_row, tr_col, ctx.vaddr);
-            softmax_tile<D>(st, acc, sm, p.c, tau, pb);
-            pin_in_phase(pb, sm.l);
-            items_prefetch<D, 0, TI::NI>(ctx);             // first V^T fragments of A(j)
-            phase_barrier();
-
-            // ---- A(j): matrix work first in line at the SIMD's issue arbiter
-            __builtin_amdgcn_s_setprio(3);
-            if (j + 3 < T) {
-                issue_tile<D, NW, false>(K, (j + 3) * KT, kv_len, stage_k((s + 3) & 3), wave, lane);
-                issue_tile<D, NW, true>(V, (j + 3) * KT, kv_len, stage_v((s + 3) & 3), wave, lane);
-            }
-            // PV(j) then QK(j+1) as one stream.  For the last tile the QK half re-reads a
-            // landed stage and its result is never used.
-            k_addresses<D>(stage_k((j + 1 < T) ? ((s + 1) & 3) : s), n, h, ctx);
-            items_run<D, 0, TI::NI>(ctx, pb, qf, acc, st);
-            mask_tail(st, (j + 1) * KT, kv_len, h);
-            __builtin_amdgcn_s_setprio(0);
-        }
-    }
-    if (group == 0) __syncthreads();              // same number of barriers for every wavefront
-
-    write_output<D>(O, acc, sm.l, qrow, qvalid, p.N, h);
-}
-
-// ---------------------------------------------------------------------------
-// Dense path, balanced phases.  Same two-group anti-phase scheme as attn_dense_pp_kernel,
-// but the work of a tile is cut so that BOTH phases carry half of the MFMAs:
-//   P1(j)  O^T += V_{j-1}^T P_{j-1}^T (16 MFMAs at D=128)  interleaved with  the softmax of
-//          S_j: row max, reference update, exp / sum / bf16 conversion -> P_j
-//   P2(j)  S_{j+1} = K_{j+1} Q^T (16 MFMAs), the tile copies
-// Between two barriers one group runs a P1 and the other a P2, so both wavefronts of a
-// SIMD feed the matrix pipe all the time and the vector work rides along with it.
-// When the reference max moves, P_j already uses the new reference while O still holds
-// tiles < j in the old one: O (including the P1(j) products, all in the old reference) is
-// rescaled at the end of P1(j), before P_j is ever multiplied in.
-// Slots (intervals between barriers): group 0 runs P1(j) in slot 2j+1 and P2(j) in slot
-// 2j+2, group 1 one slot later; a last P1(T) does the products of the last tile.
-// Copies: event E(j) = {K_{j+4}, V_{j+2}}, issued in P2(j) into the stages of K_j (last read
-// in slot 2j+1) and V_{j-2} (slot 2j).  Before every barrier a wavefront waits for all of
-// its copies except its newest event, so K_{j+1} and V_{j-1} (event E(j-3)) are complete
-// from slot 2j on: in time for the fragment prefetch at the end of the preceding phase.
-// ---------------------------------------------------------------------------
-__device__ __forceinline__ float tile_max_step(float mx, const f32x16 (&st)[2], int i)
-{
-    return fmaxf(fmaxf(mx, st[0][i]), st[1][i]);
-}
-
-// exp / sum / conversion of score values 2*CH and 2*CH+1 (flattened in MFMA-operand order:
-// value v -> pb[v / 8][v % 8] = st[(v / 8) >> 1][8 * ((v / 8) & 1) + v % 8])
-template <int CH>
-__device__ __forceinline__ void softmax_chunk(const f32x16 (&st)[2], float c, float mc, float& rs0, float& rs1,
-                                              bf16x8 (&pb)[4])
-{
-    constexpr int g = CH / 4, k = 2 * (CH % 4), rb = g >> 1, off = 8 * (g & 1) + k;
-    const float e0 = __builtin_amdgcn_exp2f(__builtin_fmaf(st[rb][off], c, -mc));
-    const float e1 = __builtin_amdgcn_exp2f(__builtin_fmaf(st[rb][off + 1], c, -mc));
-    rs0 += e0;
-    rs1 += e1;
-    pb[g][k] = (__bf16)e0;
-    pb[g][k + 1] = (__bf16)e1;
-    // values computed from registers only may be moved anywhere; tying the sums to an empty
-    // volatile statement keeps this chunk between the LDS requests it was written between
-    asm volatile("" : "+v"(rs0), "+v"(rs1));
-}
-
-template <int CH, int END>
-__device__ __forceinline__ void softmax_chunks(const f32x16 (&st)[2], float c, float mc, float& rs0, float& rs1,
-                                               bf16x8 (&pb)[4])
-{
-    if constexpr (CH < END) {
-        softmax_chunk<CH>(st, c, mc, rs0, rs1, pb);
-        softmax_chunks<CH + 1, END>(st, c, mc, rs0, rs1, pb);
-    }
-}
-
-struct P1State {
-    float mx;        // running row max of the tile being exponentiated
-    float mc;        // reference max * c
-    float alpha;     // factor the accumulators still have to be multiplied by (1 = none)
-    float rs0, rs1;  // partial row sums
-};
-
-// The VALU work attached to PV item I (of NPV): the first quarter of the items carry the
-// max steps, then the reference is updated, then half of the items carry the exp chunks.
-template <int D, int I>
-__device__ __forceinline__ void p1_valu(const f32x16 (&st)[2], SoftmaxState& sm, P1State& ps, float c, float tau,
-                                        bf16x8 (&pb_new)[4])
-{
-    constexpr int NPV = TileItems<D>::NPV;
-    constexpr int MI = NPV / 4, NE = NPV / 2;
-    constexpr int MS = 16 / MI, CS = 16 / NE;
-    if constexpr (I < MI) {
-#pragma unroll
-        for (int m = 0; m < MS; ++m) ps.mx = tile_max_step(ps.mx, st, I * MS + m);
-    }
-    if constexpr (I == MI - 1) {
-        auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(ps.mx), __float_as_uint(ps.mx), false, false);
-        const float mx = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
-        // Lazy rescale: keep the old reference while the new max exceeds it by at most tau
-        // (probabilities then stay below 2^8); any reference gives the same quotient.
-        ps.alpha = 1.0f;
-        if (__builtin_amdgcn_ballot_w64(mx > sm.m + tau) != 0ull) {
-            const float m_new = fmaxf(sm.m, mx);          // finite: every visited tile has a valid key
-            ps.alpha = __builtin_amdgcn_exp2f((sm.m - m_new) * c);
-            sm.m = m_new;
-            sm.l *= ps.alpha;
-        }
-        ps.mc = sm.m * c;
-    }
-    if constexpr (I >= MI && I < MI + NE)
-        softmax_chunks<(I - MI) * CS, (I - MI + 1) * CS>(st, c, ps.mc, ps.rs0, ps.rs1, pb_new);
-}
-
-// P1: PV items of tile j-1 interleaved with the softmax of tile j.
-template <int D, int I = 0>
-__device__ __forceinline__ void p1_steps(TileCtx<D>& ctx, const bf16x8 (&qf)[D / 16], const bf16x8 (&pb_old)[4],
-                                         f32x16 (&acc)[D / 32], f32x16 (&st)[2], SoftmaxState& sm, P1State& ps,
-                                         float c, float tau, bf16x8 (&pb_new)[4])
-{
-    typedef TileItems<D> TI;
-    if constexpr (I < TI::NPV) {
-        if constexpr (I + TI::PD < TI::NPV) item_request<D, I + TI::PD>(ctx);
-        item_wait<D, I, TI::NPV>(ctx);
-        item_mfma<D, I>(ctx, pb_old, qf, acc, st);
-        p1_valu<D, I>(st, sm, ps, c, tau, pb_new);
-        __builtin_amdgcn_sched_barrier(0);                 // keep the interleave as written
-        p1_steps<D, I + 1>(ctx, qf, pb_old, acc, st, sm, ps, c, tau, pb_new);
-    }
-}
-
-template <int D>
-__global__ __launch_bounds__(512, 2) void attn_dense_bp_kernel(const AttnParams p)
-{
-    typedef Geo<D> G;
-    typedef TileItems<D> TI;
-    constexpr int NW = 8, QT = 256, KS = D / 16, DB = D / 32;
-    constexpr int LPT = 2 * G::LOADS / NW;        // copy instructions per wavefront per event
-
-    __shared__ __attribute__((aligned(1024))) char lds[8 * G::TILE_BYTES];     // K stages 0..3, V stages 4..7
-    auto k_stage = [&](int t) -> char* { return lds + (t & 3) * G::TILE_BYTES; };
-    auto v_stage = [&](int t) -> char* { return lds + (4 + (t & 3)) * G::TILE_BYTES; };
-
-    const int wg = blockIdx.x;
-    const int item = (wg % XCDS) * p.chunk + wg / XCDS;     // XCD-aware: see attn_kernel
-    if (item >= p.items) return;
-    const int bh = item / p.nq;
-    const int qi = item % p.nq;
-
-    const int tid = threadIdx.x;
-    const int lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int group = wave >> 2;
-    const int n = lane & 31;
-    const int h = lane >> 5;
-    const int kv_len = p.kv_len;
-
-    const size_t base = (size_t)bh * p.N * D;
-    const __bf16* __restrict__ Q = p.q + base;
-    const __bf16* __restrict__ K = p.k + base;
-    const __bf16* __restrict__ V = p.v + base;
-    __bf16* __restrict__ O = p.o + base;
-
-    const int T = (kv_len + KT - 1) / KT;         // >= 1
-
-#pragma unroll
-    for (int t = 0; t < 4; ++t)
-        if (t < T) issue_tile<D, NW, false>(K, t * KT, kv_len, k_stage(t), wave, lane);
-#pragma unroll
-    for (int t = 0; t < 2; ++t)
-        if (t < T) issue_tile<D, NW, true>(V, t * KT, kv_len, v_stage(t), wave, lane);
-
-    const int qrow = qi * QT + wave * 32 + n;
-    const bool qvalid = qrow < kv_len;
-    bf16x8 qf[KS];
-    load_q<D>(Q, qrow, qvalid, h, qf);
-
-    f32x16 acc[DB];
-#pragma unroll
-    for (int i = 0; i < DB; ++i)
-#pragma unroll
-        for (int j = 0; j < 16; ++j) acc[i][j] = 0.f;
-    SoftmaxState sm;
-    sm.m = -INFINITY;
-    sm.l = 0.f;
-    const float tau = 8.0f / p.c;
-    const int tr_row = (lane & 15) >> 2;
-    const int tr_col = ((lane & 3) << 2) + (((lane >> 4) & 1) << 4);
-
-    wait_vmcnt<0>();                              // Q fragments and the first tiles
-    __syncthreads();
-    if (group == 1) __syncthreads();              // group 1 runs one barrier behind
-
-    TileCtx<D> ctx;
-    bf16x8 pba[4], pbb[4];
-    f32x16 st[2];
-    // S_0
-    k_addresses<D>(k_stage(0), n, h, ctx);
-    items_prefetch<D, TI::NPV, TI::NI>(ctx);
-    items_run<D, TI::NPV, TI::NI>(ctx, pba, qf, acc, st);
-    mask_tail(st, 0, kv_len, h);
-
-    auto slot_barrier = [&](int j) {              // all copies but the newest event E(j-1)
-        if (j + 3 < T) wait_vmcnt<LPT>();
+    for (int j = 0; j < T; ++j) {
+        // my share of tile j+1 (outstanding: tiles j+1 and j+2, completing in order)
+        if (j + 2 < T) wait_vmcnt<LPT>();
         else wait_vmcnt<0>();
         phase_barrier();
-    };
-    auto phase1_tail = [&](P1State& ps) {         // row sums, deferred rescale of O
-        sm.l += ps.rs0 + ps.rs1;
-        if (__builtin_amdgcn_ballot_w64(ps.alpha != 1.0f) != 0ull) {
-#pragma unroll
-            for (int i = 0; i < DB; ++i)
-#pragma unroll
-                for (int jj = 0; jj < 16; ++jj) acc[i][jj] *= ps.alpha;
-        }
-    };
-    // Iteration j = 0 .. T.  pb_old = P_{j-1} (consumed), pb_new = P_j (produced).  One code
-    // path for all j: at j = 0, P_{-1} = 0 is multiplied into tile 0's V (adds nothing); at
-    // j = T the "scores" are -inf, which leaves the softmax state untouched.
-    auto tile_iter = [&](int j, bf16x8 (&pb_old)[4], bf16x8 (&pb_new)[4]) {
-        slot_barrier(j);
-        // ---- P1(j): PV(j-1) with softmax(S_j)
-        if (j == T) {
-            asm volatile("");                     // a real branch, not 32 selects per tile
-#pragma unroll
-            for (int rb = 0; rb < 2; ++rb)
-#pragma unroll
-                for (int i = 0; i < 16; ++i) st[rb][i] = -INFINITY;
-        }
-        P1State ps;
-        ps.mx = st[0][0]; ps.mc = 0.f; ps.alpha = 1.0f; ps.rs0 = 0.f; ps.rs1 = 0.f;
-        p1_steps<D>(ctx, qf, pb_old, acc, st, sm, ps, p.c, tau, pb_new);
-        phase1_tail(ps);
-        pin_in_phase(pb_new, sm.l);
-        if (j + 1 < T) {
-            k_addresses<D>(k_stage(j + 1), n, h, ctx);
-            items_prefetch<D, TI::NPV, TI::NI>(ctx);  // first K_{j+1} fragments of P2(j)
-        }
-        if (j < T) {
-            slot_barrier(j);
-            // ---- P2(j): copies of E(j), S_{j+1}
-            if (j + 4 < T) issue_tile<D, NW, false>(K, (j + 4) * KT, kv_len, k_stage(j + 4), wave, lane);
-            if (j + 2 < T) issue_tile<D, NW, true>(V, (j + 2) * KT, kv_len, v_stage(j + 2), wave, lane);
-            if (j + 1 < T) {
-                items_run<D, TI::NPV, TI::NI>(ctx, pb_new, qf, acc, st);
-                mask_tail(st, (j + 1) * KT, kv_len, h);
-            }
-            v_addresses<D>(v_stage(j), h, tr_row, tr_col, ctx.vaddr);
-            items_prefetch<D, 0, TI::NPV>(ctx);   // first V_j^T fragments of P1(j+1)
-        }
-    };
 
-#pragma unroll
-    for (int g = 0; g < 4; ++g)
-#pragma unroll
-        for (int i = 0; i < 8; ++i) pbb[g][i] = (__bf16)0.f;
-    v_addresses<D>(v_stage(0), h, tr_row, tr_col, ctx.vaddr);
-    items_prefetch<D, 0, TI::NPV>(ctx);           // P1(0) multiplies zeros into V_0 (landed)
-    for (int j = 0; j <= T; j += 2) {
-        tile_iter(j, pbb, pba);
-        if (j + 1 > T) break;
-        tile_iter(j + 1, pba, pbb);
+        // ---- B(j)
+        v_addresses<D>(v_stage(j), h, tr_row, tr_col, ctx.vaddr);
+        softmax_tile<D>(st, acc, sm, p.c, tau, pb);
+        pin_in_phase(pb, sm.l);
+        items_prefetch<D, 0, TI::NI>(ctx);        // first V_j^T fragments of A(j)
+        phase_barrier();
+
+        // ---- A(j): matrix work first in line at the SIMD's issue arbiter
+        __builtin_amdgcn_s_setprio(3);
+        if (j + 3 < T) {
+            issue_tile<D, NW, false>(K, (j + 3) * KT, kv_len, k_stage(j + 3), wave, lane);
+            issue_tile<D, NW, true>(V, (j + 3) * KT, kv_len, v_stage(j + 3), wave, lane);
+        }
+        // PV(j) then QK(j+1) as one stream.  For the last tile the QK half re-reads a
+        // landed stage and its result is never used.
+        k_addresses<D>(k_stage((j + 1 < T) ? j + 1 : j), n, h, ctx);
+        items_run<D, 0, TI::NI>(ctx, pb, qf, acc, st);
+        mask_tail(st, (j + 1) * KT, kv_len, h);
+        __builtin_amdgcn_s_setprio(0);
     }
     if (group == 0) __syncthreads();              // same number of barriers for every wavefront
 
@@ -1245,14 +839,6 @@ int check_common(const void* q, const void* k, const void* v, const void* o,
     return RAPID_OK;
 }
 
-template <int D, int NW, int NS, int WPE>
-int launch_attn(const AttnParams& p, hipStream_t stream)
-{
-    const int grid = p.chunk * XCDS;
-    hipLaunchKernelGGL((attn_kernel<D, NW, NS, WPE>), dim3(grid), dim3(64 * NW), 0, stream, p);
-    return hipGetLastError() == hipSuccess ? RAPID_OK : RAPID_ERR_DEVICE;
-}
-
 }  // namespace
 
 extern "C" {
@@ -1278,24 +864,10 @@ int rapid_attn_dense(const void* q, const void* k, const void* v, void* o,
     p.block = 0; p.nb = 0; p.sub_shift = 0;
     p.c = scale * LOG2E;
     hipStream_t s = (hipStream_t)stream;
-#if DENSE_PINGPONG == 2
-    {
-        const int grid = p.chunk * XCDS;
-        if (D == 64) hipLaunchKernelGGL((attn_dense_bp_kernel<64>), dim3(grid), dim3(512), 0, s, p);
-        else hipLaunchKernelGGL((attn_dense_bp_kernel<128>), dim3(grid), dim3(512), 0, s, p);
-        return hipGetLastError() == hipSuccess ? RAPID_OK : RAPID_ERR_DEVICE;
-    }
-#elif DENSE_PINGPONG == 1
-    {
-        const int grid = p.chunk * XCDS;
-        if (D == 64) hipLaunchKernelGGL((attn_dense_pp_kernel<64>), dim3(grid), dim3(512), 0, s, p);
-        else hipLaunchKernelGGL((attn_dense_pp_kernel<128>), dim3(grid), dim3(512), 0, s, p);
-        return hipGetLastError() == hipSuccess ? RAPID_OK : RAPID_ERR_DEVICE;
-    }
-#else
-    return D == 64 ? launch_attn<64, DENSE_QT / 32, DENSE_NS, 2>(p, s)
-                   : launch_attn<128, DENSE_QT / 32, DENSE_NS, 2>(p, s);
-#endif
+    const int grid = p.chunk * XCDS;
+    if (D == 64) hipLaunchKernelGGL((attn_dense_pp_kernel<64>), dim3(grid), dim3(512), 0, s, p);
+    else hipLaunchKernelGGL((attn_dense_pp_kernel<128>), dim3(grid), dim3(512), 0, s, p);
+    return hipGetLastError() == hipSuccess ? RAPID_OK : RAPID_ERR_DEVICE;
 }
 
 int rapid_attn_block_sparse(const void* q, const void* k, const void* v, void* o,

@@ -71,6 +71,16 @@ def test_dense_any_token_count(N, kv_len, D):
     assert_close(run_dense(q, k, v, kv_len), oracle.attention(q, k, v, kv_len), "dense odd N")
 
 
+@pytest.mark.parametrize("B,H,N,D,kv_len", [(2, 9, 2048, 128, 2000), (1, 20, 2304, 64, 2250)])
+def test_dense_mid_size_every_element(B, H, N, D, kv_len):
+    """Several 256-query workgroup tiles per head, dozens of key tiles, ragged tail: every
+    element against the oracle."""
+    q, k, v = wl.make_qkv(B, H, N, D, kv_len, seed=107, pad_fill="nan")
+    got = run_dense(q, k, v, kv_len)
+    assert_close(got, oracle.attention(q, k, v, kv_len), "dense mid-size")
+    assert (got[:, :, kv_len:] == 0).all()
+
+
 def test_tiny_workload_both_masks_and_dense():
     w = wl.WORKLOADS["tiny"]
     q, k, v = w.qkv()
