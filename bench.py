@@ -53,6 +53,7 @@ def parse():
     ap.add_argument("--workload", default="flux_1024")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-sparse", action="store_true")
+    ap.add_argument("--no-mfma-probe", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain device copy of the Q tensor (known size) so that HBM "
@@ -129,6 +130,33 @@ def main():
                      "algorithmic_bytes": 4 * dq.numel() * 2,
                      "launch_ms_mean": round(ev_mean, 5), "launch_ms_min": round(ev_min, 5)},
     }
+
+    # ---- what the matrix pipe alone sustains on this machine (context for the roofline fraction):
+    # an MFMA-only loop, once on constant operands and once on this workload's kind of data.
+    # The published peak assumes the nominal clock; random bf16 operands throttle it.
+    if not args.no_mfma_probe:
+        import ctypes
+        probe = ctypes.CDLL(os.path.join(ROOT, "paper_2509_22323_amd", "libmfma_probe.so"))
+        probe.rapid_probe_mfma.argtypes = [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_size_t,
+                                           ctypes.c_int, ctypes.c_int, ctypes.c_void_p]
+        # each thread reads 256 bytes of operands: size the grid to the tensor that supplies them
+        blocks = int(min(512, dq.numel() * 2 // (256 * 256)))
+        iters = 2000
+        pout = torch.empty(blocks * 256, dtype=torch.float32, device="cuda")
+        stream = ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+        mfma_only = {}
+        ones = torch.ones(blocks * 256 * 128, dtype=torch.bfloat16, device="cuda")
+        for kind, data in (("constant_operands", ones), ("unit_normal_operands", dq)):
+            nbytes = data.numel() * data.element_size()
+            run = lambda: probe.rapid_probe_mfma(data.data_ptr(), nbytes, pout.data_ptr(), pout.numel() * 4,
+                                                 blocks, iters, stream)
+            rc = run()
+            if rc != 0:
+                raise RuntimeError(f"rapid_probe_mfma refused the launch: {rc}")
+            _, p_mean, _ = time_calls(run, 5, 2)
+            mfma_only[kind] = round(blocks * 4 * iters * 32 * 32768.0 / (p_mean * 1e-3) / 1e12, 1)
+        mfma_only["unit"] = "TFLOP/s"
+        out["mfma_only_loop"] = mfma_only
 
     if args.calibrate_copy:                        # 2 x Q bytes of HBM traffic, for counter calibration
         for _ in range(5):

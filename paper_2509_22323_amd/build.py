@@ -9,6 +9,9 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 SOURCES = [os.path.join(HERE, "csrc", "rapid_attn.hip")]
 OUT = os.path.join(HERE, "librapid_attn.so")
+# measurement aid used by bench.py only (an MFMA-only loop), kept out of the attention library
+PROBE_SOURCES = [os.path.join(HERE, "csrc", "mfma_probe.hip")]
+PROBE_OUT = os.path.join(HERE, "libmfma_probe.so")
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
@@ -25,7 +28,12 @@ FLAGS = [
 
 
 def build(verbose: bool = False, extra: list[str] | None = None, out: str = OUT) -> str:
-    cmd = [HIPCC] + FLAGS + (extra or []) + ["-o", out] + SOURCES
+    _compile(PROBE_SOURCES, PROBE_OUT, verbose, extra)
+    return _compile(SOURCES, out, verbose, extra)
+
+
+def _compile(sources, out, verbose, extra):
+    cmd = [HIPCC] + FLAGS + (extra or []) + ["-o", out] + sources
     if verbose:
         print(" ".join(cmd), flush=True)
     res = subprocess.run(cmd, capture_output=True, text=True)
