@@ -500,8 +500,10 @@ __device__ __forceinline__ void phase_barrier()
 // its share of tile j+1 before its first barrier of iteration j, i.e. before barrier 2j+2 at
 // the latest, which precedes the first use of tile j+1 (group 0's A(j)).
 // ---------------------------------------------------------------------------
+// (D = 64: 64 KB of LDS and <= 128 VGPRs, so two workgroups share a CU: four wavefronts per
+// SIMD hide more of the softmax phase, which is the longer one at D = 64.)
 template <int D>
-__global__ __launch_bounds__(512, 2) void attn_dense_pp_kernel(const AttnParams p)
+__global__ __launch_bounds__(512, (D == 64 ? 4 : 2)) void attn_dense_pp_kernel(const AttnParams p)
 {
     typedef Geo<D> G;
     typedef TileItems<D> TI;
@@ -631,7 +633,7 @@ __global__ __launch_bounds__(512, 2) void attn_dense_pp_kernel(const AttnParams 
 // offsets into one array.
 // ---------------------------------------------------------------------------
 template <int D, int WPG>
-__global__ __launch_bounds__(128 * WPG, 2) void attn_sparse_pp_kernel(const AttnParams p)
+__global__ __launch_bounds__(128 * WPG, (D == 64 && WPG == 4 ? 4 : 2)) void attn_sparse_pp_kernel(const AttnParams p)
 {
     typedef Geo<D> G;
     typedef TileItems<D> TI;
