@@ -89,7 +89,13 @@ RAPID_API int rapid_attn_dense(const void* q, const void* k, const void* v, void
  *             int32 order  [8*chunk]     launch plan, chunk = ceil(B*H/8)*nb:
  *                                        segment x holds the query-blocks of
  *                                        the (b,h) pairs with (b*H+h) % 8 == x,
- *                                        longest kept list first, then -1
+ *                                        heaviest entry first, then -1.  An
+ *                                        entry is a query-block id b*H*nb +
+ *                                        h*nb + i, or, with bit 30 set
+ *                                        (block 128 only), that id standing
+ *                                        for blocks i and i+1 (i even) which
+ *                                        both keep every live key-block and
+ *                                        are run as one 256-query dense tile
  *             int32 index  [B*H*nb*nb]   ascending kept key-blocks, row-wise;
  *                                        entries past counts[] are undefined
  *           (nb = N/block).  Each array starts at the next 256-byte boundary

@@ -97,30 +97,64 @@ __global__ __launch_bounds__(256) void compact_mask_kernel(
 // go to XCD (b*H + h) % 8, so the K/V of a head stay in one L2; inside an XCD the items
 // are ordered by kept-tile count, longest first (the dispatcher hands out workgroups in
 // id order, so this is longest-processing-time-first scheduling of a ragged batch).
-// order[x * chunk + i] = i-th item of XCD x, -1 past the end.  One workgroup per XCD:
-// counting sort over the counts (0..nb).  Items of equal count land in arbitrary order;
-// that only changes which workgroup computes an item, never its value.
+// Two adjacent query-blocks (2i, 2i+1) that both keep every live key-block (text rows, or a
+// sample whose action is "dense") become ONE entry, flagged PLAN_PAIR, of twice the weight:
+// the attention kernel runs it as a 256-query dense item, copying each K/V tile once for
+// both blocks.  order[x * chunk + i] = i-th entry of XCD x, -1 past the end.  One workgroup
+// per XCD: counting sort over the weights (0..2 nb).  Entries of equal weight land in
+// arbitrary order; that only changes which workgroup computes an item, never its value.
 // ---------------------------------------------------------------------------
-constexpr int PLAN_MAX_NB = 8184;                // 1023 * 8 bins + bin 0 fit the scan below
+constexpr int PLAN_MAX_NB = 4088;                // bins 0 .. 2*nb (a pair weighs twice) fit the scan below
+constexpr int PLAN_PAIR = 1 << 30;               // entry = first item of a pair of full rows
+constexpr int CUS_PER_XCD = 32;                  // MI355X: 256 CUs in 8 XCDs
 
 __global__ __launch_bounds__(1024) void plan_kernel(const int32_t* __restrict__ counts, int BH, int nb, int chunk,
-                                                    int32_t* __restrict__ order)
+                                                    int live, int pair_ok, int32_t* __restrict__ order)
 {
-    __shared__ int hist[PLAN_MAX_NB + 8];        // by r = nb - count (r = 0: longest list)
+    __shared__ int hist[2 * PLAN_MAX_NB + 16];   // by r = 2 nb - weight (r = 0: longest)
     __shared__ int scan[2][1024];
     const int x = blockIdx.x, tid = threadIdx.x;
     const int n_bh = (BH - x + XCDS - 1) / XCDS;  // (b,h) pairs with index % 8 == x
     const int n_items = n_bh > 0 ? n_bh * nb : 0;
     int32_t* out = order + (size_t)x * chunk;
-    for (int i = n_items + tid; i < chunk; i += 1024) out[i] = -1;
     auto item_of = [&](int i) { return ((i / nb) * XCDS + x) * nb + i % nb; };
-    if (nb > PLAN_MAX_NB) {                       // no sort: natural order
-        for (int i = tid; i < n_items; i += 1024) out[i] = item_of(i);
+    if (nb > PLAN_MAX_NB) {                       // no sort, no pairs: natural order
+        for (int i = tid; i < chunk; i += 1024) out[i] = i < n_items ? item_of(i) : -1;
         return;
     }
-    for (int r = tid; r < PLAN_MAX_NB + 8; r += 1024) hist[r] = 0;
+    // entry and weight of local item i; weight < 0: the second half of a pair (no entry)
+    auto classify = [&](int i, int& entry, int& weight) {
+        const int item = item_of(i), j = i % nb;
+        const int c = counts[item];
+        entry = item;
+        weight = c;
+        if (pair_ok && c == live) {
+            if ((j & 1) == 0) {
+                if (j + 1 < nb && counts[item + 1] == live) { entry = item | PLAN_PAIR; weight = 2 * live; }
+            } else if (counts[item - 1] == live) {
+                weight = -1;
+            }
+        }
+    };
+    for (int i = tid; i < chunk; i += 1024) out[i] = -1;
+    for (int r = tid; r < 2 * PLAN_MAX_NB + 16; r += 1024) hist[r] = 0;
+    __shared__ unsigned long long total;          // kept key-blocks of this XCD's items
+    if (tid == 0) total = 0ull;
     __syncthreads();
-    for (int i = tid; i < n_items; i += 1024) atomicAdd(&hist[nb - counts[item_of(i)]], 1);
+    {
+        unsigned long long mine = 0ull;
+        for (int i = tid; i < n_items; i += 1024) mine += (unsigned long long)counts[item_of(i)];
+        atomicAdd(&total, mine);
+    }
+    __syncthreads();
+    // A pair is one unit of twice the length: only worth it while that stays well below
+    // the average load of a CU, otherwise the pair itself becomes the critical path.
+    if (8ull * (unsigned long long)live * CUS_PER_XCD > 3ull * total) pair_ok = 0;
+    for (int i = tid; i < n_items; i += 1024) {
+        int entry, weight;
+        classify(i, entry, weight);
+        if (weight >= 0) atomicAdd(&hist[2 * nb - weight], 1);
+    }
     __syncthreads();
     // exclusive prefix over r: thread t owns bins 8t .. 8t+7
     int own[8], sum = 0;
@@ -140,8 +174,9 @@ __global__ __launch_bounds__(1024) void plan_kernel(const int32_t* __restrict__ 
     for (int j = 0; j < 8; ++j) { hist[8 * tid + j] = run; run += own[j]; }
     __syncthreads();
     for (int i = tid; i < n_items; i += 1024) {
-        const int item = item_of(i);
-        out[atomicAdd(&hist[nb - counts[item]], 1)] = item;
+        int entry, weight;
+        classify(i, entry, weight);
+        if (weight >= 0) out[atomicAdd(&hist[2 * nb - weight], 1)] = entry;
     }
 }
 
@@ -500,30 +535,18 @@ __device__ __forceinline__ void phase_barrier()
 // its share of tile j+1 before its first barrier of iteration j, i.e. before barrier 2j+2 at
 // the latest, which precedes the first use of tile j+1 (group 0's A(j)).
 // ---------------------------------------------------------------------------
-// (D = 64: 64 KB of LDS and <= 128 VGPRs, so two workgroups share a CU: four wavefronts per
-// SIMD hide more of the softmax phase, which is the longer one at D = 64.)
+// The body, for the 256 queries starting at row q0 of (sample, head) bh.  `lds` = 8 tile
+// stages: K stages 0..3, V stages 4..7; tile t lives in stage t % 4.  All LDS traffic of the
+// loop is explicit assembly, so the stages are plain runtime offsets into one array.
 template <int D>
-__global__ __launch_bounds__(512, (D == 64 ? 4 : 2)) void attn_dense_pp_kernel(const AttnParams p)
+__device__ __forceinline__ void dense_item(const AttnParams& p, char* lds, int bh, int q0)
 {
     typedef Geo<D> G;
     typedef TileItems<D> TI;
-    constexpr int NW = 8, QT = DENSE_QT, KS = D / 16, DB = D / 32;
+    constexpr int NW = 8, KS = D / 16, DB = D / 32;
     constexpr int LPT = 2 * G::LOADS / NW;        // copy instructions per wavefront per tile (K + V)
-
-    // All LDS traffic of the loop is explicit assembly, so the stages are plain runtime
-    // offsets into one array: K stages 0..3, V stages 4..7; tile t lives in stage t % 4.
-    __shared__ __attribute__((aligned(1024))) char lds[8 * G::TILE_BYTES];
     auto k_stage = [&](int t) -> char* { return lds + (t & 3) * G::TILE_BYTES; };
     auto v_stage = [&](int t) -> char* { return lds + (4 + (t & 3)) * G::TILE_BYTES; };
-
-    // XCD-aware work mapping: the dispatcher deals consecutive workgroup ids round-robin
-    // over the 8 XCDs, so give each XCD a contiguous run of items (query tiles of the same
-    // head then share K/V in that XCD's L2).
-    const int wg = blockIdx.x;
-    const int item = (wg % XCDS) * p.chunk + wg / XCDS;
-    if (item >= p.items) return;
-    const int bh = item / p.nq;
-    const int qi = item % p.nq;
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -549,7 +572,7 @@ __global__ __launch_bounds__(512, (D == 64 ? 4 : 2)) void attn_dense_pp_kernel(c
         }
     }
 
-    const int qrow = qi * QT + wave * 32 + n;     // this lane's query row
+    const int qrow = q0 + wave * 32 + n;          // this lane's query row
     const bool qvalid = qrow < kv_len;            // kv_len <= N
     bf16x8 qf[KS];
     load_q<D>(Q, qrow, qvalid, h, qf);
@@ -611,6 +634,21 @@ __global__ __launch_bounds__(512, (D == 64 ? 4 : 2)) void attn_dense_pp_kernel(c
     write_output<D>(O, acc, sm.l, qrow, qvalid, p.N, h);
 }
 
+// (D = 64: 64 KB of LDS and <= 128 VGPRs, so two workgroups share a CU: four wavefronts per
+// SIMD hide more of the softmax phase, which is the longer one at D = 64.)
+template <int D>
+__global__ __launch_bounds__(512, (D == 64 ? 4 : 2)) void attn_dense_pp_kernel(const AttnParams p)
+{
+    __shared__ __attribute__((aligned(1024))) char lds[8 * Geo<D>::TILE_BYTES];
+    // XCD-aware work mapping: the dispatcher deals consecutive workgroup ids round-robin
+    // over the 8 XCDs, so give each XCD a contiguous run of items (query tiles of the same
+    // head then share K/V in that XCD's L2).
+    const int wg = blockIdx.x;
+    const int item = (wg % XCDS) * p.chunk + wg / XCDS;
+    if (item >= p.items) return;
+    dense_item<D>(p, lds, item / p.nq, (item % p.nq) * DENSE_QT);
+}
+
 // ---------------------------------------------------------------------------
 // Sparse path: one workgroup per (b, h, query-block); its kept-tile list is split between
 // two wavefront groups (even tiles -> group 0, odd tiles -> group 1) that work on the SAME
@@ -646,10 +684,19 @@ __global__ __launch_bounds__(128 * WPG, (D == 64 && WPG == 4 ? 4 : 2)) void attn
 
     typedef const __attribute__((address_space(4))) int32_t* cptr_t;
     const int wg = blockIdx.x;
-    const int item = ((cptr_t)p.order)[(size_t)(wg % XCDS) * p.chunk + wg / XCDS];
-    if (item < 0) return;
+    const int entry = ((cptr_t)p.order)[(size_t)(wg % XCDS) * p.chunk + wg / XCDS];
+    if (entry < 0) return;
+    const int item = entry & ~PLAN_PAIR;
     const int bh = item / p.nq;
     const int qi = item % p.nq;
+    if constexpr (WPG == 4) {
+        // Two adjacent query-blocks that both keep every live tile: one 256-query dense item
+        // (each K/V tile is copied once for both blocks).
+        if (entry & PLAN_PAIR) {
+            dense_item<D>(p, lds, bh, qi * QT);
+            return;
+        }
+    }
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -900,7 +947,8 @@ int rapid_attn_block_sparse(const void* q, const void* k, const void* v, void* o
                        mask, (int)rows, nb, block, kv_len, counts, index);
     if (hipGetLastError() != hipSuccess) return RAPID_ERR_DEVICE;
     const int chunk = plan_chunk(B, H, nb);
-    hipLaunchKernelGGL(plan_kernel, dim3(XCDS), dim3(1024), 0, s, counts, B * H, nb, chunk, order);
+    hipLaunchKernelGGL(plan_kernel, dim3(XCDS), dim3(1024), 0, s, counts, B * H, nb, chunk,
+                       (kv_len + block - 1) / block, block == 128 ? 1 : 0, order);
     if (hipGetLastError() != hipSuccess) return RAPID_ERR_DEVICE;
 
     AttnParams p{};

@@ -114,6 +114,50 @@ def test_custom_scale_and_peaky_inputs():
     assert np.sqrt(((got - ref) ** 2).sum() / (ref ** 2).sum()) <= 1e-2
 
 
+def read_plan(ws, B, H, nb):
+    rows = B * H * nb
+    up = lambda x: (x + 255) // 256 * 256
+    chunk = (B * H + 7) // 8 * nb
+    off_order = up(rows * 4)
+    off_index = off_order + up(8 * chunk * 4)
+    counts = ws[:rows * 4].view(np.int32)
+    order = ws[off_order:off_order + 8 * chunk * 4].view(np.int32).reshape(8, chunk)
+    index = ws[off_index:off_index + rows * nb * 4].view(np.int32).reshape(rows, nb)
+    return counts, order, index
+
+
+def check_plan(counts, order, B, H, nb, block, kv_len):
+    """Every item exactly once (a flagged entry stands for a pair of adjacent query-blocks that
+    both keep every live key-block), grouped by (b,h) % 8, heaviest first, -1 padded; pairs are
+    formed exactly when block = 128 and twice the full length stays below 3/8 of the XCD's
+    kept blocks per CU (32 CUs per XCD)."""
+    PAIR = 1 << 30
+    rows = B * H * nb
+    live = (kv_len + block - 1) // block
+    covered, n_pairs = [], 0
+    for x in range(8):
+        seg = order[x]
+        ent = seg[seg >= 0]
+        assert (seg[len(ent):] == -1).all()
+        items = ent & ~PAIR
+        paired = (ent & PAIR) != 0
+        assert ((items // nb) % 8 == x).all()
+        weights = np.where(paired, 2 * live, counts[items])
+        assert (np.diff(weights) <= 0).all()
+        mine = np.array([i for i in range(rows) if (i // nb) % 8 == x], dtype=np.int64)
+        pair_ok = block == 128 and 8 * live * 32 <= 3 * int(counts[mine].sum())
+        for it, pr in zip(items.tolist(), paired.tolist()):
+            covered.append(it)
+            j = it % nb
+            full_pair = (j % 2 == 0 and j + 1 < nb and counts[it] == live and counts[it + 1] == live)
+            assert pr == (pair_ok and full_pair), (x, it, pr, pair_ok, full_pair)
+            if pr:
+                covered.append(it + 1)
+                n_pairs += 1
+    assert sorted(covered) == list(range(rows))
+    return n_pairs
+
+
 def test_compaction_is_bit_exact():
     B, H, N, D, block, kv_len = 2, 3, 1152, 64, 128, 1100
     q, k, v = wl.make_qkv(B, H, N, D, kv_len, seed=106)
@@ -123,26 +167,28 @@ def test_compaction_is_bit_exact():
     _, ws = run_sparse(q, k, v, mask, block, kv_len, return_ws=True)
     nb = N // block
     rows = B * H * nb
-    up = lambda x: (x + 255) // 256 * 256
-    chunk = (B * H + 7) // 8 * nb
-    off_order = up(rows * 4)
-    off_index = off_order + up(8 * chunk * 4)
-    counts = ws[:rows * 4].view(np.int32)
-    order = ws[off_order:off_order + 8 * chunk * 4].view(np.int32).reshape(8, chunk)
-    index = ws[off_index:off_index + rows * nb * 4].view(np.int32).reshape(rows, nb)
+    counts, order, index = read_plan(ws, B, H, nb)
     want_counts, want_index = oracle.kept_tiles(mask, block, kv_len)
     np.testing.assert_array_equal(counts, want_counts.reshape(-1))
     want_index = want_index.reshape(rows, nb)
     for r in range(rows):
         np.testing.assert_array_equal(index[r, :counts[r]], want_index[r, :counts[r]])
-    # launch plan: every item exactly once, grouped by (b,h) % 8, longest lists first, -1 padded
-    assert sorted(order[order >= 0].tolist()) == list(range(rows))
-    for x in range(8):
-        seg = order[x]
-        live = seg[seg >= 0]
-        assert (seg[len(live):] == -1).all()
-        assert ((live // nb) % 8 == x).all()
-        assert (np.diff(counts[live]) <= 0).all()
+    check_plan(counts, order, B, H, nb, block, kv_len)
+
+
+def test_launch_plan_pairs_full_rows_when_the_batch_is_large():
+    B, H, N, D, block, kv_len = 5, 8, 2304, 64, 128, 2250
+    q, k, v = wl.make_qkv(B, H, N, D, kv_len, seed=108)
+    nb = N // block
+    mask = np.ones((B, H, nb, nb), np.uint8)
+    mask[0, :, 1, 3] = 0                                   # one row per head of sample 0 is not full
+    got, ws = run_sparse(q, k, v, mask, block, kv_len, return_ws=True)
+    counts, order, _ = read_plan(ws, B, H, nb)
+    np.testing.assert_array_equal(counts, oracle.kept_tiles(mask, block, kv_len)[0].reshape(-1))
+    assert check_plan(counts, order, B, H, nb, block, kv_len) > 0
+    rows_ = wl.sample_rows(B, H, N, kv_len, block, 96, seed=5)
+    ref = oracle.attention_rows(q, k, v, rows_, kv_len, mask, block)
+    assert_close(got[rows_[:, 0], rows_[:, 1], rows_[:, 2]], ref, "paired full rows")
 
 
 # ---------------------------------------------------------------- full sizes, sampled rows
