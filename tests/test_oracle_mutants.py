@@ -22,7 +22,9 @@ MUTANTS = [
     ("mask_transposed", "mask + ((size_t)bh * nb + (size_t)(r / block)) * nb : NULL;\n            attn_row(q + base + (size_t)r * D, k + base, v + base, mrow, block,\n                     kv_len, D, scale, score, out);\n        }\n        free(score);\n    }\n    return failed ? -7 : 0;\n}\n\n/*\n * Selected",
      "mask + ((size_t)bh * nb + (size_t)(r / block)) : NULL;\n            attn_row(q + base + (size_t)r * D, k + base, v + base, mrow, block,\n                     kv_len, D, scale, score, out);\n        }\n        free(score);\n    }\n    return failed ? -7 : 0;\n}\n\n/*\n * Selected"),
     ("mask_block_index_by_row", "(mask_row[c / block] != 0)", "(mask_row[c % block % 2] != 0)"),
-    ("pad_keys_included", "for (c = 0; c < kv_len; ++c) {\n        int allowed", "for (c = 0; c < kv_len + 1; ++c) {\n        int allowed"),
+    # every loop of the row routine runs over all N allocated keys (stays inside the arrays)
+    ("pad_keys_included", "                     kv_len, D, scale, score, out);\n        }\n        free(score);\n    }\n    return failed ? -7 : 0;\n}\n\n/*\n * Selected",
+     "                     N, D, scale, score, out);\n        }\n        free(score);\n    }\n    return failed ? -7 : 0;\n}\n\n/*\n * Selected"),
     ("k_transposed_index", "bf16_to_f64(k[(size_t)c * D + d]);", "bf16_to_f64(k[(size_t)d * D + c]);"),
     ("v_wrong_row", "out[d] += p * bf16_to_f64(v[(size_t)c * D + d]);", "out[d] += p * bf16_to_f64(v[(size_t)(c ^ 1) * D + d]);"),
     ("softmax_sign", "score[c] = exp(score[c] - m);", "score[c] = exp(m - score[c]);"),
