@@ -82,25 +82,39 @@ RAPID_API int rapid_attn_dense(const void* q, const void* k, const void* v, void
  *           as the sparsity control is per layer and per head.
  *   workspace  device scratch of at least rapid_attn_workspace_bytes(...)
  *           bytes, 16-byte aligned.  The call first compacts the mask into
- *           it, then runs attention over the kept tiles only:
+ *           it, then runs attention over the kept tiles only.  With
+ *           nb = N/block, items = ceil(B*H/8)*nb, and each array starting at
+ *           the next 256-byte boundary after the previous one:
  *             int32 counts [B*H*nb]      kept key-blocks of each query-block
  *                                        (blocks starting at or beyond kv_len
  *                                        are dropped)
- *             int32 order  [8*chunk]     launch plan, chunk = ceil(B*H/8)*nb:
- *                                        segment x holds the query-blocks of
- *                                        the (b,h) pairs with (b*H+h) % 8 == x,
- *                                        heaviest entry first, then -1.  An
- *                                        entry is a query-block id b*H*nb +
- *                                        h*nb + i, or, with bit 30 set
- *                                        (block 128 only), that id standing
- *                                        for blocks i and i+1 (i even) which
- *                                        both keep every live key-block and
- *                                        are run as one 256-query dense tile
+ *             launch plan, 8 segments of `chunk` entries: segment x holds the
+ *                                        work of the (b,h) pairs with
+ *                                        (b*H+h) % 8 == x, longest entry
+ *                                        first, then entries meaning "none"
+ *               block 64:  chunk = items; entry = int32 item id
+ *                          b*H*nb + h*nb + i, none = -1
+ *               block 128: chunk = items + pmax; entry = 4 x int32
+ *                          (item, first, n, w): n kept key-blocks of the item
+ *                          starting at position `first` of its list; none =
+ *                          (-1,0,0,-1).  w = -1 for a whole item.  An item
+ *                          with more kept blocks than the XCD's total divided
+ *                          by slots (resident workgroups per XCD: 64 at
+ *                          D=128, 128 at D=64) is cut into
+ *                          P = min(16, ceil(c / max(4, total/(2*slots))))
+ *                          pieces [c*k/P, c*(k+1)/P) whose partial results
+ *                          are added up in piece order;
+ *                          w = (slot << 8) | (k << 4) | (P-1), the slots
+ *                          (pmax = min(2*slots, items) per XCD) handed out in
+ *                          item order; an item that no longer fits stays
+ *                          whole.
  *             int32 index  [B*H*nb*nb]   ascending kept key-blocks, row-wise;
  *                                        entries past counts[] are undefined
- *           (nb = N/block).  Each array starts at the next 256-byte boundary
- *           after the previous one.  Contents are outputs of the call; the
- *           layout is stated so tests can check the compaction bit-for-bit.
+ *             block 128 only: int32 arrived [8*pmax] and the partial-result
+ *                                        slots [8*pmax] of 64 KB + 2 KB
+ *                                        (D=128) or 32 KB + 2 KB (D=64)
+ *           Contents are outputs of the call; the layout is stated so tests
+ *           can check the compaction and the plan bit for bit.
  *   other arguments as rapid_attn_dense.
  */
 RAPID_API int rapid_attn_block_sparse(const void* q, const void* k, const void* v, void* o,

@@ -56,8 +56,10 @@ struct AttnParams {
     const __bf16* v;
     __bf16* o;
     const int32_t* counts;   // sparse: kept key-blocks per (b,h,query-block); dense: null
-    const int32_t* order;    // sparse: launch order of (b,h,query-block) items
+    const int32_t* order;    // sparse: launch plan (64-token tiles: item ids; 128-token tiles: PlanRec records)
     const int32_t* index;    // sparse: kept key-block lists, nb per row
+    int32_t* arrived;        // sparse, 128-token tiles: finished pieces per split item
+    char* partial;           // sparse, 128-token tiles: partial results of the pieces of split items
     int H, N, kv_len;
     int nq;                  // query tiles per (sample, head)
     int items;               // B*H*nq
@@ -93,70 +95,19 @@ __global__ __launch_bounds__(256) void compact_mask_kernel(
 }
 
 // ---------------------------------------------------------------------------
-// Launch plan of the sparse path.  Items = (b, h, query-block).  All items of one (b,h)
-// go to XCD (b*H + h) % 8, so the K/V of a head stay in one L2; inside an XCD the items
-// are ordered by kept-tile count, longest first (the dispatcher hands out workgroups in
-// id order, so this is longest-processing-time-first scheduling of a ragged batch).
-// Two adjacent query-blocks (2i, 2i+1) that both keep every live key-block (text rows, or a
-// sample whose action is "dense") become ONE entry, flagged PLAN_PAIR, of twice the weight:
-// the attention kernel runs it as a 256-query dense item, copying each K/V tile once for
-// both blocks.  order[x * chunk + i] = i-th entry of XCD x, -1 past the end.  One workgroup
-// per XCD: counting sort over the weights (0..2 nb).  Entries of equal weight land in
-// arbitrary order; that only changes which workgroup computes an item, never its value.
+// Launch plans of the sparse path.  Items = (b, h, query-block).  All items of one (b,h)
+// go to XCD (b*H + h) % 8, so the K/V of a head stay in one L2; inside an XCD the entries
+// are ordered by length, longest first (the dispatcher hands out workgroups in id order, so
+// this is longest-processing-time-first scheduling of a ragged batch).  One workgroup per
+// XCD: counting sort over the lengths.  Entries of equal length land in arbitrary order;
+// that only changes which workgroup computes an entry, never its value.
 // ---------------------------------------------------------------------------
-constexpr int PLAN_MAX_NB = 4088;                // bins 0 .. 2*nb (a pair weighs twice) fit the scan below
-constexpr int PLAN_PAIR = 1 << 30;               // entry = first item of a pair of full rows
-constexpr int CUS_PER_XCD = 32;                  // MI355X: 256 CUs in 8 XCDs
+constexpr int PLAN_MAX_NB = 8176;                // bins 0 .. nb fit the scan below
+constexpr int PLAN_BINS = 8192;                  // 8 bins per thread
 
-__global__ __launch_bounds__(1024) void plan_kernel(const int32_t* __restrict__ counts, int BH, int nb, int chunk,
-                                                    int live, int pair_ok, int32_t* __restrict__ order)
+// Exclusive prefix sum of hist[0 .. PLAN_BINS) in place (1024 threads, thread t owns bins 8t..8t+7).
+__device__ __forceinline__ void plan_scan_bins(int* hist, int (*scan)[1024], int tid)
 {
-    __shared__ int hist[2 * PLAN_MAX_NB + 16];   // by r = 2 nb - weight (r = 0: longest)
-    __shared__ int scan[2][1024];
-    const int x = blockIdx.x, tid = threadIdx.x;
-    const int n_bh = (BH - x + XCDS - 1) / XCDS;  // (b,h) pairs with index % 8 == x
-    const int n_items = n_bh > 0 ? n_bh * nb : 0;
-    int32_t* out = order + (size_t)x * chunk;
-    auto item_of = [&](int i) { return ((i / nb) * XCDS + x) * nb + i % nb; };
-    if (nb > PLAN_MAX_NB) {                       // no sort, no pairs: natural order
-        for (int i = tid; i < chunk; i += 1024) out[i] = i < n_items ? item_of(i) : -1;
-        return;
-    }
-    // entry and weight of local item i; weight < 0: the second half of a pair (no entry)
-    auto classify = [&](int i, int& entry, int& weight) {
-        const int item = item_of(i), j = i % nb;
-        const int c = counts[item];
-        entry = item;
-        weight = c;
-        if (pair_ok && c == live) {
-            if ((j & 1) == 0) {
-                if (j + 1 < nb && counts[item + 1] == live) { entry = item | PLAN_PAIR; weight = 2 * live; }
-            } else if (counts[item - 1] == live) {
-                weight = -1;
-            }
-        }
-    };
-    for (int i = tid; i < chunk; i += 1024) out[i] = -1;
-    for (int r = tid; r < 2 * PLAN_MAX_NB + 16; r += 1024) hist[r] = 0;
-    __shared__ unsigned long long total;          // kept key-blocks of this XCD's items
-    if (tid == 0) total = 0ull;
-    __syncthreads();
-    {
-        unsigned long long mine = 0ull;
-        for (int i = tid; i < n_items; i += 1024) mine += (unsigned long long)counts[item_of(i)];
-        atomicAdd(&total, mine);
-    }
-    __syncthreads();
-    // A pair is one unit of twice the length: only worth it while that stays well below
-    // the average load of a CU, otherwise the pair itself becomes the critical path.
-    if (8ull * (unsigned long long)live * CUS_PER_XCD > 3ull * total) pair_ok = 0;
-    for (int i = tid; i < n_items; i += 1024) {
-        int entry, weight;
-        classify(i, entry, weight);
-        if (weight >= 0) atomicAdd(&hist[2 * nb - weight], 1);
-    }
-    __syncthreads();
-    // exclusive prefix over r: thread t owns bins 8t .. 8t+7
     int own[8], sum = 0;
 #pragma unroll
     for (int j = 0; j < 8; ++j) { own[j] = hist[8 * tid + j]; sum += own[j]; }
@@ -173,10 +124,151 @@ __global__ __launch_bounds__(1024) void plan_kernel(const int32_t* __restrict__ 
 #pragma unroll
     for (int j = 0; j < 8; ++j) { hist[8 * tid + j] = run; run += own[j]; }
     __syncthreads();
+}
+
+// 64-token mask tiles: order[x * chunk + i] = i-th item of XCD x, -1 past the end.
+__global__ __launch_bounds__(1024) void plan_kernel(const int32_t* __restrict__ counts, int BH, int nb, int chunk,
+                                                    int32_t* __restrict__ order)
+{
+    __shared__ int hist[PLAN_BINS];              // by r = nb - count (r = 0: longest)
+    __shared__ int scan[2][1024];
+    const int x = blockIdx.x, tid = threadIdx.x;
+    const int n_bh = (BH - x + XCDS - 1) / XCDS;  // (b,h) pairs with index % 8 == x
+    const int n_items = n_bh > 0 ? n_bh * nb : 0;
+    int32_t* out = order + (size_t)x * chunk;
+    auto item_of = [&](int i) { return ((i / nb) * XCDS + x) * nb + i % nb; };
+    if (nb > PLAN_MAX_NB) {                       // no sort: natural order
+        for (int i = tid; i < chunk; i += 1024) out[i] = i < n_items ? item_of(i) : -1;
+        return;
+    }
+    for (int i = tid; i < chunk; i += 1024) out[i] = -1;
+    for (int r = tid; r < PLAN_BINS; r += 1024) hist[r] = 0;
+    __syncthreads();
+    for (int i = tid; i < n_items; i += 1024) atomicAdd(&hist[nb - counts[item_of(i)]], 1);
+    __syncthreads();
+    plan_scan_bins(hist, scan, tid);
     for (int i = tid; i < n_items; i += 1024) {
-        int entry, weight;
-        classify(i, entry, weight);
-        if (weight >= 0) out[atomicAdd(&hist[2 * nb - weight], 1)] = entry;
+        const int item = item_of(i);
+        out[atomicAdd(&hist[nb - counts[item]], 1)] = item;
+    }
+}
+
+// 128-token mask tiles: the plan is a list of records, one per workgroup.  An item whose kept
+// list is longer than the average load of a workgroup slot of its XCD (kept key-blocks of
+// the XCD / resident workgroups of the XCD) would be the critical path of the launch, so it
+// is cut into P pieces of about half that average (at least SPLIT_MIN_BLOCKS key-blocks, at
+// most SPLIT_MAX_PIECES pieces), each a record of its own; the pieces leave partial results
+// in the workspace and the last one to finish combines them.  Partial-result slots are
+// handed out in item order (a prefix sum, so the plan does not depend on timing); an item
+// that no longer fits in the XCD's pmax slots stays whole.
+struct PlanRec {
+    int item;     // b*H*nb + h*nb + query-block, or -1: no work
+    int blk0;     // first position of the piece in the item's kept list
+    int nblk;     // kept key-blocks of the piece
+    int w;        // -1: the whole item; else (first partial slot << 8) | (piece << 4) | (P - 1)
+};
+constexpr int SPLIT_MIN_BLOCKS = 4;
+constexpr int SPLIT_MAX_PIECES = 16;
+
+__device__ __forceinline__ int split_pieces(int c, unsigned long long total, int slots)
+{
+    if ((unsigned long long)c * (unsigned)slots <= total) return 1;        // not above the average
+    const unsigned long long half = total / (2ull * (unsigned)slots);
+    const int target = half > (unsigned long long)SPLIT_MIN_BLOCKS ? (int)half : SPLIT_MIN_BLOCKS;
+    const int P = (c + target - 1) / target;
+    return P < SPLIT_MAX_PIECES ? P : SPLIT_MAX_PIECES;
+}
+
+__global__ __launch_bounds__(1024) void plan_split_kernel(const int32_t* __restrict__ counts, int BH, int nb, int cap,
+                                                          int slots, int pmax, PlanRec* __restrict__ recs,
+                                                          int32_t* __restrict__ arrived)
+{
+    __shared__ int hist[PLAN_BINS];              // by r = nb - length (r = 0: longest)
+    __shared__ int scan[2][1024];
+    __shared__ unsigned long long total;          // kept key-blocks of this XCD's items
+    const int x = blockIdx.x, tid = threadIdx.x;
+    const int n_bh = (BH - x + XCDS - 1) / XCDS;
+    const int n_items = n_bh > 0 ? n_bh * nb : 0;
+    PlanRec* out = recs + (size_t)x * cap;
+    auto item_of = [&](int i) { return ((i / nb) * XCDS + x) * nb + i % nb; };
+    const PlanRec none = {-1, 0, 0, -1};
+    for (int i = tid; i < pmax; i += 1024) arrived[(size_t)x * pmax + i] = 0;
+    if (nb > PLAN_MAX_NB) {                       // no sort, no pieces: natural order
+        for (int i = tid; i < cap; i += 1024) {
+            PlanRec r = none;
+            if (i < n_items) { r.item = item_of(i); r.nblk = counts[r.item]; }
+            out[i] = r;
+        }
+        return;
+    }
+    for (int i = tid; i < cap; i += 1024) out[i] = none;
+    for (int r = tid; r < PLAN_BINS; r += 1024) hist[r] = 0;
+    if (tid == 0) total = 0ull;
+    __syncthreads();
+    {
+        unsigned long long mine = 0ull;
+        for (int i = tid; i < n_items; i += 1024) mine += (unsigned long long)counts[item_of(i)];
+        atomicAdd(&total, mine);
+    }
+    __syncthreads();
+    const unsigned long long tot = total;
+    // partial-result slots in item order: thread t owns the items [lo, hi)
+    const int per = (n_items + 1023) / 1024;
+    const int lo = tid * per < n_items ? tid * per : n_items;
+    const int hi = lo + per < n_items ? lo + per : n_items;
+    int mine = 0;
+    for (int i = lo; i < hi; ++i) {
+        const int P = split_pieces(counts[item_of(i)], tot, slots);
+        if (P > 1) mine += P;
+    }
+    scan[0][tid] = mine;
+    __syncthreads();
+    int cur = 0;
+    for (int d = 1; d < 1024; d <<= 1) {
+        const int v = scan[cur][tid] + (tid >= d ? scan[cur][tid - d] : 0);
+        scan[cur ^ 1][tid] = v;
+        cur ^= 1;
+        __syncthreads();
+    }
+    const int first_slot = scan[cur][tid] - mine;
+    __syncthreads();
+    // pieces of item i: P (1 = whole) and the first partial slot
+    auto pieces_of = [&](int c, int& run, int& P, int& slot0) {
+        const int want = split_pieces(c, tot, slots);
+        P = want;
+        slot0 = -1;
+        if (want > 1) {
+            if (run + want <= pmax) slot0 = run; else P = 1;
+            run += want;                          // the prefix counts every candidate
+        }
+    };
+    {
+        int run = first_slot;
+        for (int i = lo; i < hi; ++i) {
+            const int c = counts[item_of(i)];
+            int P, slot0;
+            pieces_of(c, run, P, slot0);
+            for (int k = 0; k < P; ++k) atomicAdd(&hist[nb - (c * (k + 1) / P - c * k / P)], 1);
+        }
+    }
+    __syncthreads();
+    plan_scan_bins(hist, scan, tid);
+    {
+        int run = first_slot;
+        for (int i = lo; i < hi; ++i) {
+            const int item = item_of(i);
+            const int c = counts[item];
+            int P, slot0;
+            pieces_of(c, run, P, slot0);
+            for (int k = 0; k < P; ++k) {
+                PlanRec r;
+                r.item = item;
+                r.blk0 = c * k / P;
+                r.nblk = c * (k + 1) / P - r.blk0;
+                r.w = (P > 1) ? (((x * pmax + slot0) << 8) | (k << 4) | (P - 1)) : -1;
+                out[atomicAdd(&hist[nb - r.nblk], 1)] = r;
+            }
+        }
     }
 }
 
@@ -684,19 +776,10 @@ __global__ __launch_bounds__(128 * WPG, (D == 64 && WPG == 4 ? 4 : 2)) void attn
 
     typedef const __attribute__((address_space(4))) int32_t* cptr_t;
     const int wg = blockIdx.x;
-    const int entry = ((cptr_t)p.order)[(size_t)(wg % XCDS) * p.chunk + wg / XCDS];
-    if (entry < 0) return;
-    const int item = entry & ~PLAN_PAIR;
+    const int item = ((cptr_t)p.order)[(size_t)(wg % XCDS) * p.chunk + wg / XCDS];
+    if (item < 0) return;
     const int bh = item / p.nq;
     const int qi = item % p.nq;
-    if constexpr (WPG == 4) {
-        // Two adjacent query-blocks that both keep every live tile: one 256-query dense item
-        // (each K/V tile is copied once for both blocks).
-        if (entry & PLAN_PAIR) {
-            dense_item<D>(p, lds, bh, qi * QT);
-            return;
-        }
-    }
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -851,27 +934,252 @@ __global__ __launch_bounds__(128 * WPG, (D == 64 && WPG == 4 ? 4 : 2)) void attn
     }
 }
 
+// Partial result of one piece of a split item: the fp32 accumulators in register order
+// ([wavefront][register pair][lane], 8 bytes each), then (m, l) per lane.
+template <int D>
+struct PartialSlot {
+    static constexpr size_t ML_OFF = (size_t)4 * (D / 32) * 4 * 64 * 16;      // 64 KB | 32 KB
+    static constexpr size_t BYTES = ML_OFF + 4 * 64 * 2 * 4;                  // + 2 KB
+};
+
+// ---------------------------------------------------------------------------
+// Sparse path, 128-token mask tiles: one workgroup of FOUR wavefronts per (b, h, query-block)
+// walks the whole kept-tile list of its item; 64 KB of LDS (32 KB at D = 64) and one
+// wavefront per SIMD, so two such workgroups (four at D = 64) share a CU.  The fixed cost
+// of an item (list lookup, first copies, Q load, output) is then hidden behind the tile loop
+// of the neighbour instead of leaving the CU idle, which is what matters when the lists are
+// short; the two wavefronts on a SIMD belong to different items and fall into the same
+// softmax-against-MFMA overlap as the two groups of the dense kernel.
+//
+// Per tile j two slots separated by workgroup barriers:
+//   B(j)  softmax of S_j; copies of V_{j+1} and K_{j+2} issued; first V_j^T fragments requested
+//   A(j)  O^T += V_j^T P_j^T ; S_{j+1} = K_{j+1} Q^T
+// LDS: K stages 0,1 and V stages 2,3; tile t in stage t % 2.  When B(j) starts every
+// wavefront has finished A(j-1), the last reader of V_{j-1} and K_j, whose stages take
+// V_{j+1} and K_{j+2}.  Copies complete in issue order, so "all but the newest n" is a wait
+// for everything older: K_{j+1} (issued in B(j-1)) is awaited at the end of B(j) with this
+// slot's copies still in flight, V_{j+1} at the end of A(j) with K_{j+2} still in flight.
+// ---------------------------------------------------------------------------
+template <int D>
+__global__ __launch_bounds__(256, (D == 64 ? 4 : 2)) void attn_sparse_sg_kernel(const AttnParams p)
+{
+    typedef Geo<D> G;
+    typedef TileItems<D> TI;
+    constexpr int NW = 4, QT = 128, KS = D / 16, DB = D / 32;
+    constexpr int LPT = G::LOADS / NW;            // copy instructions per wavefront per tile (K or V)
+
+    __shared__ __attribute__((aligned(1024))) char lds[4 * G::TILE_BYTES];
+
+    typedef const __attribute__((address_space(4))) int32_t* cptr_t;
+    const int wg = blockIdx.x;
+    typedef int i32x4 __attribute__((ext_vector_type(4)));
+    typedef const __attribute__((address_space(4))) i32x4* rptr_t;
+    static_assert(sizeof(PlanRec) == sizeof(i32x4), "one record = one 16-byte scalar load");
+    const i32x4 raw = ((rptr_t)p.order)[(size_t)(wg % XCDS) * p.chunk + wg / XCDS];
+    const PlanRec rec = {raw[0], raw[1], raw[2], raw[3]};
+    const int item = rec.item;
+    if (item < 0) return;
+    const int bh = item / p.nq;
+    const int qi = item % p.nq;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int n = lane & 31;
+    const int h = lane >> 5;
+    const int kv_len = p.kv_len;
+
+    const size_t base = (size_t)bh * p.N * D;
+    const __bf16* __restrict__ Q = p.q + base;
+    const __bf16* __restrict__ K = p.k + base;
+    const __bf16* __restrict__ V = p.v + base;
+    __bf16* __restrict__ O = p.o + base;
+
+    const int qrow = qi * QT + wave * 32 + n;
+    const bool qvalid = qrow < kv_len;
+
+    // 64-key tiles of this piece (two per kept 128-key block; the item's last block may have one)
+    cptr_t list = (cptr_t)(p.index + (size_t)item * p.nb + rec.blk0);
+    int T = rec.nblk * 2;
+    if (rec.nblk > 0 && (list[rec.nblk - 1] * 2 + 1) * KT >= kv_len) T -= 1;
+    f32x16 acc[DB];
+#pragma unroll
+    for (int i = 0; i < DB; ++i)
+#pragma unroll
+        for (int j = 0; j < 16; ++j) acc[i][j] = 0.f;
+    if (T <= 0) {                                 // nothing kept: the rows are zero
+        write_output<D>(O, acc, 0.f, qrow, false, p.N, h);
+        return;
+    }
+    auto key_of = [&](int t) -> int { return (list[t >> 1] * 2 + (t & 1)) * KT; };
+    auto k_stage = [&](int t) -> char* { return lds + (t & 1) * G::TILE_BYTES; };
+    auto v_stage = [&](int t) -> char* { return lds + (2 + (t & 1)) * G::TILE_BYTES; };
+    // first keys of tiles j+1, j+2, j+3 (0 past the end), fetched ahead of their use
+    const int key0 = key_of(0);
+    int kn1 = (1 < T) ? key_of(1) : 0;
+    int kn2 = (2 < T) ? key_of(2) : 0;
+    int kn3 = (3 < T) ? key_of(3) : 0;
+
+    issue_tile<D, NW, false>(K, key0, kv_len, k_stage(0), wave, lane);
+    issue_tile<D, NW, true>(V, key0, kv_len, v_stage(0), wave, lane);
+    if (1 < T) issue_tile<D, NW, false>(K, kn1, kv_len, k_stage(1), wave, lane);
+
+    bf16x8 qf[KS];
+    load_q<D>(Q, qrow, qvalid, h, qf);
+    SoftmaxState sm;
+    sm.m = -INFINITY;
+    sm.l = 0.f;
+    const float tau = 8.0f / p.c;
+    const int tr_row = (lane & 15) >> 2;
+    const int tr_col = ((lane & 3) << 2) + (((lane >> 4) & 1) << 4);
+    wait_vmcnt<0>();
+    __syncthreads();
+
+    TileCtx<D> ctx;
+    bf16x8 pb[4];
+    f32x16 st[2];
+    k_addresses<D>(k_stage(0), n, h, ctx);
+    items_prefetch<D, TI::NPV, TI::NI>(ctx);
+    items_run<D, TI::NPV, TI::NI>(ctx, pb, qf, acc, st);   // S_0
+    mask_tail(st, key0, kv_len, h);
+
+    for (int j = 0; j < T; ++j) {
+        phase_barrier();                          // A(j-1) (or S_0) finished by every wavefront; V_j landed
+
+        // ---- B(j)
+        if (j + 1 < T) issue_tile<D, NW, true>(V, kn1, kv_len, v_stage(j + 1), wave, lane);
+        if (j + 2 < T) issue_tile<D, NW, false>(K, kn2, kv_len, k_stage(j), wave, lane);
+        v_addresses<D>(v_stage(j), h, tr_row, tr_col, ctx.vaddr);
+        softmax_tile<D>(st, acc, sm, p.c, tau, pb);
+        pin_in_phase(pb, sm.l);
+        items_prefetch<D, 0, TI::NI>(ctx);        // first V_j^T fragments of A(j)
+        if (j + 2 < T) wait_vmcnt<2 * LPT>();     // K_{j+1} landed
+        else if (j + 1 < T) wait_vmcnt<LPT>();
+        else wait_vmcnt<0>();
+        phase_barrier();
+
+        // ---- A(j): PV(j) then QK(j+1) as one stream (without a tile j+1 the QK half re-reads
+        // K_j, which is still in its stage, and its result is never used)
+        __builtin_amdgcn_s_setprio(3);
+        k_addresses<D>(k_stage((j + 1 < T) ? j + 1 : j), n, h, ctx);
+        items_run<D, 0, TI::NI>(ctx, pb, qf, acc, st);
+        mask_tail(st, kn1, kv_len, h);
+        __builtin_amdgcn_s_setprio(0);
+        if (j + 2 < T) wait_vmcnt<LPT>();         // V_{j+1} landed
+        else wait_vmcnt<0>();
+        kn1 = kn2; kn2 = kn3;
+        kn3 = (j + 4 < T) ? key_of(j + 4) : 0;
+    }
+
+    if (rec.w < 0) {                              // the whole item
+        write_output<D>(O, acc, sm.l, qrow, qvalid, p.N, h);
+        return;
+    }
+
+    // ---- a piece of a split item: leave (acc, m, l) in this piece's slot; the piece that
+    // finishes last adds all of them up, in piece order (so the sum does not depend on which
+    // one that is).  A piece has at least one valid key per query, so every m is finite.
+    // The slots are written and read with device-scope relaxed atomic accesses, each of which
+    // is coherent across the chip by itself, instead of plain accesses between device-scope
+    // fences: a release fence would write back every dirty line of the XCD's L2.  Order: a
+    // wavefront's stores are acknowledged (vmcnt 0) before the barrier after which one thread
+    // counts the piece in; the last piece reads only after it has seen the full count.
+    typedef unsigned long long u64;
+    constexpr size_t SLOT_BYTES = PartialSlot<D>::BYTES;
+    constexpr int PAIRS = DB * 8;                 // 64-bit words of accumulators per lane
+    const int P = (rec.w & 15) + 1;
+    const int piece = (rec.w >> 4) & 15;
+    const int slot0 = rec.w >> 8;
+    auto slot_acc = [&](int k) -> u64* { return (u64*)(p.partial + (size_t)(slot0 + k) * SLOT_BYTES) + (size_t)wave * PAIRS * 64 + lane; };
+    auto slot_ml = [&](int k) -> u64* { return (u64*)(p.partial + (size_t)(slot0 + k) * SLOT_BYTES + PartialSlot<D>::ML_OFF) + wave * 64 + lane; };
+    {
+        u64* pacc = slot_acc(piece);
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const u64 v = (u64)__float_as_uint(acc[db][2 * j]) | ((u64)__float_as_uint(acc[db][2 * j + 1]) << 32);
+                __hip_atomic_store(pacc + (db * 8 + j) * 64, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+        const u64 ml = (u64)__float_as_uint(sm.m) | ((u64)__float_as_uint(sm.l) << 32);
+        __hip_atomic_store(slot_ml(piece), ml, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    __shared__ int arrived_before;
+    wait_vmcnt<0>();
+    __syncthreads();
+    if (tid == 0) arrived_before = __hip_atomic_fetch_add(&p.arrived[slot0], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __syncthreads();
+    if (arrived_before != P - 1) return;
+
+    float m = -INFINITY;
+    for (int k = 0; k < P; ++k) {
+        const u64 ml = __hip_atomic_load(slot_ml(k), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        m = fmaxf(m, __uint_as_float((unsigned)ml));
+    }
+#pragma unroll
+    for (int i = 0; i < DB; ++i)
+#pragma unroll
+        for (int j = 0; j < 16; ++j) acc[i][j] = 0.f;
+    float l = 0.f;
+    for (int k = 0; k < P; ++k) {
+        const u64 ml = __hip_atomic_load(slot_ml(k), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const float a = __builtin_amdgcn_exp2f((__uint_as_float((unsigned)ml) - m) * p.c);
+        l += __uint_as_float((unsigned)(ml >> 32)) * a;
+        const u64* pacc = slot_acc(k);
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const u64 v = __hip_atomic_load(pacc + (db * 8 + j) * 64, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                acc[db][2 * j] += __uint_as_float((unsigned)v) * a;
+                acc[db][2 * j + 1] += __uint_as_float((unsigned)(v >> 32)) * a;
+            }
+    }
+    write_output<D>(O, acc, l, qrow, qvalid, p.N, h);
+}
+
 // ---------------------------------------------------------------------------
 // Host side
 // ---------------------------------------------------------------------------
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 struct WorkspaceLayout {
-    size_t counts_off, order_off, index_off, total;
+    size_t counts_off, order_off, index_off, arrived_off, partial_off, total;
+    int chunk;    // plan entries per XCD
+    int slots;    // resident workgroups per XCD the plan balances for (128-token tiles)
+    int pmax;     // partial-result slots per XCD (128-token tiles)
 };
 
-// items of one XCD in the launch plan: (b,h) pairs are dealt round-robin over the XCDs
-inline int plan_chunk(int B, int H, int nb) { return ((B * H + XCDS - 1) / XCDS) * nb; }
+// items of one XCD: (b,h) pairs are dealt round-robin over the XCDs
+inline int plan_items(int B, int H, int nb) { return ((B * H + XCDS - 1) / XCDS) * nb; }
 
-inline WorkspaceLayout workspace_layout(int B, int H, int nb)
+// 64-token tiles:  counts | order int32[8*chunk]   | index
+// 128-token tiles: counts | records PlanRec[8*chunk] | index | arrived int32[8*pmax] | partial slots [8*pmax]
+inline WorkspaceLayout workspace_layout(int B, int H, int nb, int D, int block)
 {
     const size_t rows = (size_t)B * H * nb;
     auto up = [](size_t x) { return (x + 255) & ~(size_t)255; };
     WorkspaceLayout w;
+    const int items = plan_items(B, H, nb);
     w.counts_off = 0;
     w.order_off = up(rows * 4);
-    w.index_off = w.order_off + up((size_t)XCDS * plan_chunk(B, H, nb) * 4);
-    w.total = w.index_off + up(rows * (size_t)nb * 4);
+    if (block == 128) {
+        // 32 CUs per XCD, two resident workgroups per CU at D = 128 and four at D = 64
+        w.slots = 32 * (D == 64 ? 4 : 2);
+        w.pmax = 2 * w.slots < items ? 2 * w.slots : items;
+        w.chunk = items + w.pmax;
+        w.index_off = w.order_off + up((size_t)XCDS * w.chunk * sizeof(PlanRec));
+        w.arrived_off = w.index_off + up(rows * (size_t)nb * 4);
+        w.partial_off = w.arrived_off + up((size_t)XCDS * w.pmax * 4);
+        const size_t slot = D == 64 ? PartialSlot<64>::BYTES : PartialSlot<128>::BYTES;
+        w.total = w.partial_off + up((size_t)XCDS * w.pmax * slot);
+    } else {
+        w.slots = 0;
+        w.pmax = 0;
+        w.chunk = items;
+        w.index_off = w.order_off + up((size_t)XCDS * w.chunk * 4);
+        w.arrived_off = w.partial_off = w.total = w.index_off + up(rows * (size_t)nb * 4);
+    }
     return w;
 }
 
@@ -932,7 +1240,7 @@ int rapid_attn_block_sparse(const void* q, const void* k, const void* v, void* o
     const int nb = N / block;
     const long long rows = (long long)B * H * nb;
     if (rows > 0x7fffffffLL / 16) return RAPID_ERR_SHAPE;
-    const WorkspaceLayout w = workspace_layout(B, H, nb);
+    const WorkspaceLayout w = workspace_layout(B, H, nb, D, block);
     if (!workspace || workspace_bytes < w.total) return RAPID_ERR_WORKSPACE;
     if (!aligned16(workspace)) return RAPID_ERR_ALIGN;
     if (!(scale > 0.f)) scale = 1.0f / sqrtf((float)D);
@@ -946,24 +1254,28 @@ int rapid_attn_block_sparse(const void* q, const void* k, const void* v, void* o
     hipLaunchKernelGGL(compact_mask_kernel, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, s,
                        mask, (int)rows, nb, block, kv_len, counts, index);
     if (hipGetLastError() != hipSuccess) return RAPID_ERR_DEVICE;
-    const int chunk = plan_chunk(B, H, nb);
-    hipLaunchKernelGGL(plan_kernel, dim3(XCDS), dim3(1024), 0, s, counts, B * H, nb, chunk,
-                       (kv_len + block - 1) / block, block == 128 ? 1 : 0, order);
+    if (block == 128)
+        hipLaunchKernelGGL(plan_split_kernel, dim3(XCDS), dim3(1024), 0, s, counts, B * H, nb, w.chunk, w.slots,
+                           w.pmax, (PlanRec*)order, (int32_t*)(ws + w.arrived_off));
+    else
+        hipLaunchKernelGGL(plan_kernel, dim3(XCDS), dim3(1024), 0, s, counts, B * H, nb, w.chunk, order);
     if (hipGetLastError() != hipSuccess) return RAPID_ERR_DEVICE;
 
     AttnParams p{};
     p.q = (const __bf16*)q; p.k = (const __bf16*)k; p.v = (const __bf16*)v; p.o = (__bf16*)o;
     p.counts = counts; p.order = order; p.index = index;
+    p.arrived = (int32_t*)(ws + w.arrived_off);
+    p.partial = ws + w.partial_off;
     p.H = H; p.N = N; p.kv_len = kv_len;
     p.nq = nb;
     p.items = (int)rows;
-    p.chunk = chunk;
+    p.chunk = w.chunk;
     p.block = block; p.nb = nb; p.sub_shift = block == 128 ? 1 : 0;
     p.c = scale * LOG2E;
-    const dim3 grid((unsigned)chunk * XCDS);
+    const dim3 grid((unsigned)w.chunk * XCDS);
     if (block == 128) {
-        if (D == 64) hipLaunchKernelGGL((attn_sparse_pp_kernel<64, 4>), grid, dim3(512), 0, s, p);
-        else hipLaunchKernelGGL((attn_sparse_pp_kernel<128, 4>), grid, dim3(512), 0, s, p);
+        if (D == 64) hipLaunchKernelGGL((attn_sparse_sg_kernel<64>), grid, dim3(256), 0, s, p);
+        else hipLaunchKernelGGL((attn_sparse_sg_kernel<128>), grid, dim3(256), 0, s, p);
     } else {
         if (D == 64) hipLaunchKernelGGL((attn_sparse_pp_kernel<64, 2>), grid, dim3(256), 0, s, p);
         else hipLaunchKernelGGL((attn_sparse_pp_kernel<128, 2>), grid, dim3(256), 0, s, p);
@@ -978,7 +1290,7 @@ size_t rapid_attn_workspace_bytes(int B, int H, int N, int D, int block)
     if (block != 64 && block != 128) return 0;
     if (N % block != 0 || N > (1 << 22)) return 0;
     if ((long long)B * H * (N / block) > 0x7fffffffLL / 16) return 0;
-    return workspace_layout(B, H, N / block).total;
+    return workspace_layout(B, H, N / block, D, block).total;
 }
 
 const char* rapid_attn_status_string(int status)

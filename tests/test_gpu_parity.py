@@ -114,48 +114,79 @@ def test_custom_scale_and_peaky_inputs():
     assert np.sqrt(((got - ref) ** 2).sum() / (ref ** 2).sum()) <= 1e-2
 
 
-def read_plan(ws, B, H, nb):
-    rows = B * H * nb
+def plan_geometry(B, H, nb, D, block):
+    """Workspace geometry of the sparse entry point, as its header states it."""
     up = lambda x: (x + 255) // 256 * 256
-    chunk = (B * H + 7) // 8 * nb
-    off_order = up(rows * 4)
-    off_index = off_order + up(8 * chunk * 4)
-    counts = ws[:rows * 4].view(np.int32)
-    order = ws[off_order:off_order + 8 * chunk * 4].view(np.int32).reshape(8, chunk)
-    index = ws[off_index:off_index + rows * nb * 4].view(np.int32).reshape(rows, nb)
-    return counts, order, index
-
-
-def check_plan(counts, order, B, H, nb, block, kv_len):
-    """Every item exactly once (a flagged entry stands for a pair of adjacent query-blocks that
-    both keep every live key-block), grouped by (b,h) % 8, heaviest first, -1 padded; pairs are
-    formed exactly when block = 128 and twice the full length stays below 3/8 of the XCD's
-    kept blocks per CU (32 CUs per XCD)."""
-    PAIR = 1 << 30
     rows = B * H * nb
-    live = (kv_len + block - 1) // block
-    covered, n_pairs = [], 0
+    items = (B * H + 7) // 8 * nb
+    if block == 128:
+        slots = 32 * (4 if D == 64 else 2)
+        pmax = min(2 * slots, items)
+        chunk = items + pmax
+        rec_bytes = 16
+    else:
+        slots, pmax, chunk, rec_bytes = 0, 0, items, 4
+    off_order = up(rows * 4)
+    off_index = off_order + up(8 * chunk * rec_bytes)
+    return dict(rows=rows, slots=slots, pmax=pmax, chunk=chunk, off_order=off_order, off_index=off_index)
+
+
+def read_plan(ws, B, H, nb, D, block):
+    g = plan_geometry(B, H, nb, D, block)
+    rows, chunk = g["rows"], g["chunk"]
+    counts = ws[:rows * 4].view(np.int32)
+    width = 4 if block == 128 else 1
+    order = ws[g["off_order"]:g["off_order"] + 8 * chunk * 4 * width].view(np.int32).reshape(8, chunk, width)
+    index = ws[g["off_index"]:g["off_index"] + rows * nb * 4].view(np.int32).reshape(rows, nb)
+    return counts, order, index, g
+
+
+def split_pieces(c, total, slots):
+    if c * slots <= total:
+        return 1
+    target = max(4, total // (2 * slots))
+    return min(16, (c + target - 1) // target)
+
+
+def check_plan(counts, order, g, B, H, nb, block):
+    """The launch plan, entry for entry.  Every XCD segment holds the entries of the (b,h) pairs
+    with (b*H+h) % 8 == x, longest first, then -1.  With 64-token tiles an entry is an item; with
+    128-token tiles it is a record (item, first list position, kept blocks, w) and an item longer
+    than the average load of a workgroup slot is cut into pieces by the rule in the header."""
+    rows = B * H * nb
+    n_split = 0
     for x in range(8):
         seg = order[x]
-        ent = seg[seg >= 0]
-        assert (seg[len(ent):] == -1).all()
-        items = ent & ~PAIR
-        paired = (ent & PAIR) != 0
-        assert ((items // nb) % 8 == x).all()
-        weights = np.where(paired, 2 * live, counts[items])
-        assert (np.diff(weights) <= 0).all()
-        mine = np.array([i for i in range(rows) if (i // nb) % 8 == x], dtype=np.int64)
-        pair_ok = block == 128 and 8 * live * 32 <= 3 * int(counts[mine].sum())
-        for it, pr in zip(items.tolist(), paired.tolist()):
-            covered.append(it)
-            j = it % nb
-            full_pair = (j % 2 == 0 and j + 1 < nb and counts[it] == live and counts[it + 1] == live)
-            assert pr == (pair_ok and full_pair), (x, it, pr, pair_ok, full_pair)
-            if pr:
-                covered.append(it + 1)
-                n_pairs += 1
-    assert sorted(covered) == list(range(rows))
-    return n_pairs
+        valid = seg[:, 0] >= 0
+        n = int(valid.sum())
+        assert valid[:n].all() and (seg[n:, 0] == -1).all()
+        ent = seg[:n]
+        mine = [i for i in range(rows) if (i // nb) % 8 == x]          # ascending item id
+        assert ((ent[:, 0] // nb) % 8 == x).all()
+        if block != 128:
+            assert sorted(ent[:, 0].tolist()) == mine
+            assert (np.diff(counts[ent[:, 0]]) <= 0).all()
+            continue
+        assert (np.diff(ent[:, 2]) <= 0).all()
+        total = int(counts[mine].sum())
+        want, run = [], 0
+        for it in mine:
+            c = int(counts[it])
+            P = split_pieces(c, total, g["slots"])
+            slot0 = -1
+            if P > 1:
+                if run + P <= g["pmax"]:
+                    slot0 = run
+                run += P
+                if slot0 < 0:
+                    P = 1
+            for k in range(P):
+                b0 = c * k // P
+                w = ((x * g["pmax"] + slot0) << 8 | k << 4 | (P - 1)) if P > 1 else -1
+                want.append((it, b0, c * (k + 1) // P - b0, w))
+            n_split += P > 1
+        assert sorted(map(tuple, ent.tolist())) == sorted(want)
+    return n_split
 
 
 def test_compaction_is_bit_exact():
@@ -167,28 +198,51 @@ def test_compaction_is_bit_exact():
     _, ws = run_sparse(q, k, v, mask, block, kv_len, return_ws=True)
     nb = N // block
     rows = B * H * nb
-    counts, order, index = read_plan(ws, B, H, nb)
+    counts, order, index, g = read_plan(ws, B, H, nb, D, block)
     want_counts, want_index = oracle.kept_tiles(mask, block, kv_len)
     np.testing.assert_array_equal(counts, want_counts.reshape(-1))
     want_index = want_index.reshape(rows, nb)
     for r in range(rows):
         np.testing.assert_array_equal(index[r, :counts[r]], want_index[r, :counts[r]])
-    check_plan(counts, order, B, H, nb, block, kv_len)
+    check_plan(counts, order, g, B, H, nb, block)
 
 
-def test_launch_plan_pairs_full_rows_when_the_batch_is_large():
-    B, H, N, D, block, kv_len = 5, 8, 2304, 64, 128, 2250
-    q, k, v = wl.make_qkv(B, H, N, D, kv_len, seed=108)
+def test_compaction_is_bit_exact_with_64_token_tiles():
+    B, H, N, D, block, kv_len = 2, 5, 576, 64, 64, 530
+    q, k, v = wl.make_qkv(B, H, N, D, kv_len, seed=107)
     nb = N // block
-    mask = np.ones((B, H, nb, nb), np.uint8)
-    mask[0, :, 1, 3] = 0                                   # one row per head of sample 0 is not full
+    mask = wl.mask_bernoulli_diag(B, H, nb, 0.5, seed=10)
+    _, ws = run_sparse(q, k, v, mask, block, kv_len, return_ws=True)
+    counts, order, index, g = read_plan(ws, B, H, nb, D, block)
+    want_counts, want_index = oracle.kept_tiles(mask, block, kv_len)
+    np.testing.assert_array_equal(counts, want_counts.reshape(-1))
+    for r in range(B * H * nb):
+        np.testing.assert_array_equal(index[r, :counts[r]], want_index.reshape(-1, nb)[r, :counts[r]])
+    check_plan(counts, order, g, B, H, nb, block)
+
+
+@pytest.mark.parametrize("D", [64, 128])
+def test_long_rows_are_split_into_pieces_and_merged(D):
+    """A few rows keep every tile while the rest keep few: the long rows exceed the average
+    load of a workgroup slot, are cut into pieces and combined by the last piece to finish.
+    The ragged tail block (kv_len inside it) is the last block of the last piece."""
+    B, H, N, block, kv_len = 2, 8, 4608, 128, 4500
+    nb = N // block
+    q, k, v = wl.make_qkv(B, H, N, D, kv_len, seed=108 + D)
+    mask = wl.mask_bernoulli_diag(B, H, nb, 0.08, seed=12)
+    mask[:, :, 5, :] = 1
+    mask[:, :, nb - 1, :] = 1
+    mask[1, :, 17, ::2] = 1
     got, ws = run_sparse(q, k, v, mask, block, kv_len, return_ws=True)
-    counts, order, _ = read_plan(ws, B, H, nb)
+    counts, order, _, g = read_plan(ws, B, H, nb, D, block)
     np.testing.assert_array_equal(counts, oracle.kept_tiles(mask, block, kv_len)[0].reshape(-1))
-    assert check_plan(counts, order, B, H, nb, block, kv_len) > 0
-    rows_ = wl.sample_rows(B, H, N, kv_len, block, 96, seed=5)
+    assert check_plan(counts, order, g, B, H, nb, block) >= 2 * B * H
+    rng = np.random.default_rng(3)
+    rows_ = np.stack([rng.integers(B, size=160), rng.integers(H, size=160),
+                      rng.choice(np.r_[5 * block:6 * block, (nb - 1) * block:kv_len, 17 * block:18 * block,
+                                       0:block], size=160)], axis=1).astype(np.int32)
     ref = oracle.attention_rows(q, k, v, rows_, kv_len, mask, block)
-    assert_close(got[rows_[:, 0], rows_[:, 1], rows_[:, 2]], ref, "paired full rows")
+    assert_close(got[rows_[:, 0], rows_[:, 1], rows_[:, 2]], ref, "split rows")
 
 
 # ---------------------------------------------------------------- full sizes, sampled rows
