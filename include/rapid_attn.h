@@ -98,14 +98,15 @@ RAPID_API int rapid_attn_dense(const void* q, const void* k, const void* v, void
  *                          (item, first, n, w): n kept key-blocks of the item
  *                          starting at position `first` of its list; none =
  *                          (-1,0,0,-1).  w = -1 for a whole item.  An item
- *                          with more kept blocks than the XCD's total divided
- *                          by slots (resident workgroups per XCD: 64 at
- *                          D=128, 128 at D=64) is cut into
- *                          P = min(16, ceil(c / max(4, total/(2*slots))))
- *                          pieces [c*k/P, c*(k+1)/P) whose partial results
+ *                          with c kept blocks, in an XCD whose items keep
+ *                          `total` blocks, is cut into
+ *                          P = max(1, min(round(c*192/total), c/8, 16))
+ *                          pieces [c*k/P, c*(k+1)/P) (192 = 32 CUs x 6:
+ *                          pieces of about a sixth of a CU's share, at
+ *                          least 8 key-blocks each) whose partial results
  *                          are added up in piece order;
  *                          w = (slot << 8) | (k << 4) | (P-1), the slots
- *                          (pmax = min(2*slots, items) per XCD) handed out in
+ *                          (pmax = min(256, items) per XCD) handed out in
  *                          item order; an item that no longer fits stays
  *                          whole.
  *             int32 index  [B*H*nb*nb]   ascending kept key-blocks, row-wise;

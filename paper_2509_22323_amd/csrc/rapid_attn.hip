@@ -153,11 +153,12 @@ __global__ __launch_bounds__(1024) void plan_kernel(const int32_t* __restrict__ 
     }
 }
 
-// 128-token mask tiles: the plan is a list of records, one per workgroup.  An item whose kept
-// list is longer than the average load of a workgroup slot of its XCD (kept key-blocks of
-// the XCD / resident workgroups of the XCD) would be the critical path of the launch, so it
-// is cut into P pieces of about half that average (at least SPLIT_MIN_BLOCKS key-blocks, at
-// most SPLIT_MAX_PIECES pieces), each a record of its own; the pieces leave partial results
+// 128-token mask tiles: the plan is a list of records, one per workgroup.  The dispatcher
+// fills the CUs entry by entry, so the entries have to be small against a CU's share of the
+// work or the last ones leave most of the chip idle: an item is cut into P pieces of about
+// 1/SPLIT_PER_CU of that share (kept key-blocks of the XCD / its CUs), but of at least
+// SPLIT_MIN_BLOCKS key-blocks each so that the fixed cost of an entry stays small, and into at
+// most SPLIT_MAX_PIECES.  Each piece is a record of its own; the pieces leave partial results
 // in the workspace and the last one to finish combines them.  Partial-result slots are
 // handed out in item order (a prefix sum, so the plan does not depend on timing); an item
 // that no longer fits in the XCD's pmax slots stays whole.
@@ -167,20 +168,26 @@ struct PlanRec {
     int nblk;     // kept key-blocks of the piece
     int w;        // -1: the whole item; else (first partial slot << 8) | (piece << 4) | (P - 1)
 };
-constexpr int SPLIT_MIN_BLOCKS = 4;
+constexpr int CUS_PER_XCD = 32;                  // MI355X: 256 CUs in 8 XCDs
+constexpr int SPLIT_PER_CU = 6;
+constexpr int SPLIT_MIN_BLOCKS = 8;
 constexpr int SPLIT_MAX_PIECES = 16;
+constexpr int SPLIT_SLOTS = 256;                 // partial-result slots per XCD (the rule needs < 256)
 
-__device__ __forceinline__ int split_pieces(int c, unsigned long long total, int slots)
+// P = round(c / target), target = total / (CUS_PER_XCD * SPLIT_PER_CU), within the limits above
+__device__ __forceinline__ int split_pieces(int c, unsigned long long total)
 {
-    if ((unsigned long long)c * (unsigned)slots <= total) return 1;        // not above the average
-    const unsigned long long half = total / (2ull * (unsigned)slots);
-    const int target = half > (unsigned long long)SPLIT_MIN_BLOCKS ? (int)half : SPLIT_MIN_BLOCKS;
-    const int P = (c + target - 1) / target;
-    return P < SPLIT_MAX_PIECES ? P : SPLIT_MAX_PIECES;
+    if (total == 0ull) return 1;
+    const unsigned long long g = (unsigned long long)CUS_PER_XCD * SPLIT_PER_CU;
+    unsigned long long P = (2ull * (unsigned)c * g + total) / (2ull * total);
+    const unsigned long long by_len = (unsigned)c / SPLIT_MIN_BLOCKS;
+    if (P > by_len) P = by_len;
+    if (P > (unsigned long long)SPLIT_MAX_PIECES) P = SPLIT_MAX_PIECES;
+    return P < 1ull ? 1 : (int)P;
 }
 
 __global__ __launch_bounds__(1024) void plan_split_kernel(const int32_t* __restrict__ counts, int BH, int nb, int cap,
-                                                          int slots, int pmax, PlanRec* __restrict__ recs,
+                                                          int pmax, PlanRec* __restrict__ recs,
                                                           int32_t* __restrict__ arrived)
 {
     __shared__ int hist[PLAN_BINS];              // by r = nb - length (r = 0: longest)
@@ -218,7 +225,7 @@ __global__ __launch_bounds__(1024) void plan_split_kernel(const int32_t* __restr
     const int hi = lo + per < n_items ? lo + per : n_items;
     int mine = 0;
     for (int i = lo; i < hi; ++i) {
-        const int P = split_pieces(counts[item_of(i)], tot, slots);
+        const int P = split_pieces(counts[item_of(i)], tot);
         if (P > 1) mine += P;
     }
     scan[0][tid] = mine;
@@ -234,7 +241,7 @@ __global__ __launch_bounds__(1024) void plan_split_kernel(const int32_t* __restr
     __syncthreads();
     // pieces of item i: P (1 = whole) and the first partial slot
     auto pieces_of = [&](int c, int& run, int& P, int& slot0) {
-        const int want = split_pieces(c, tot, slots);
+        const int want = split_pieces(c, tot);
         P = want;
         slot0 = -1;
         if (want > 1) {
@@ -1146,7 +1153,6 @@ inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 
 struct WorkspaceLayout {
     size_t counts_off, order_off, index_off, arrived_off, partial_off, total;
     int chunk;    // plan entries per XCD
-    int slots;    // resident workgroups per XCD the plan balances for (128-token tiles)
     int pmax;     // partial-result slots per XCD (128-token tiles)
 };
 
@@ -1164,9 +1170,7 @@ inline WorkspaceLayout workspace_layout(int B, int H, int nb, int D, int block)
     w.counts_off = 0;
     w.order_off = up(rows * 4);
     if (block == 128) {
-        // 32 CUs per XCD, two resident workgroups per CU at D = 128 and four at D = 64
-        w.slots = 32 * (D == 64 ? 4 : 2);
-        w.pmax = 2 * w.slots < items ? 2 * w.slots : items;
+        w.pmax = SPLIT_SLOTS < items ? SPLIT_SLOTS : items;
         w.chunk = items + w.pmax;
         w.index_off = w.order_off + up((size_t)XCDS * w.chunk * sizeof(PlanRec));
         w.arrived_off = w.index_off + up(rows * (size_t)nb * 4);
@@ -1174,7 +1178,6 @@ inline WorkspaceLayout workspace_layout(int B, int H, int nb, int D, int block)
         const size_t slot = D == 64 ? PartialSlot<64>::BYTES : PartialSlot<128>::BYTES;
         w.total = w.partial_off + up((size_t)XCDS * w.pmax * slot);
     } else {
-        w.slots = 0;
         w.pmax = 0;
         w.chunk = items;
         w.index_off = w.order_off + up((size_t)XCDS * w.chunk * 4);
@@ -1255,7 +1258,7 @@ int rapid_attn_block_sparse(const void* q, const void* k, const void* v, void* o
                        mask, (int)rows, nb, block, kv_len, counts, index);
     if (hipGetLastError() != hipSuccess) return RAPID_ERR_DEVICE;
     if (block == 128)
-        hipLaunchKernelGGL(plan_split_kernel, dim3(XCDS), dim3(1024), 0, s, counts, B * H, nb, w.chunk, w.slots,
+        hipLaunchKernelGGL(plan_split_kernel, dim3(XCDS), dim3(1024), 0, s, counts, B * H, nb, w.chunk,
                            w.pmax, (PlanRec*)order, (int32_t*)(ws + w.arrived_off));
     else
         hipLaunchKernelGGL(plan_kernel, dim3(XCDS), dim3(1024), 0, s, counts, B * H, nb, w.chunk, order);

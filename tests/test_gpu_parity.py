@@ -120,15 +120,14 @@ def plan_geometry(B, H, nb, D, block):
     rows = B * H * nb
     items = (B * H + 7) // 8 * nb
     if block == 128:
-        slots = 32 * (4 if D == 64 else 2)
-        pmax = min(2 * slots, items)
+        pmax = min(256, items)
         chunk = items + pmax
         rec_bytes = 16
     else:
-        slots, pmax, chunk, rec_bytes = 0, 0, items, 4
+        pmax, chunk, rec_bytes = 0, items, 4
     off_order = up(rows * 4)
     off_index = off_order + up(8 * chunk * rec_bytes)
-    return dict(rows=rows, slots=slots, pmax=pmax, chunk=chunk, off_order=off_order, off_index=off_index)
+    return dict(rows=rows, pmax=pmax, chunk=chunk, off_order=off_order, off_index=off_index)
 
 
 def read_plan(ws, B, H, nb, D, block):
@@ -141,18 +140,19 @@ def read_plan(ws, B, H, nb, D, block):
     return counts, order, index, g
 
 
-def split_pieces(c, total, slots):
-    if c * slots <= total:
+def split_pieces(c, total):
+    """Pieces of an item with c kept key-blocks when its XCD holds `total`: round(c / target) with
+    target = total / (32 CUs x 6), at most c // 8 (a piece has at least 8 key-blocks) and 16."""
+    if total == 0:
         return 1
-    target = max(4, total // (2 * slots))
-    return min(16, (c + target - 1) // target)
+    return max(1, min((2 * c * 192 + total) // (2 * total), c // 8, 16))
 
 
 def check_plan(counts, order, g, B, H, nb, block):
     """The launch plan, entry for entry.  Every XCD segment holds the entries of the (b,h) pairs
     with (b*H+h) % 8 == x, longest first, then -1.  With 64-token tiles an entry is an item; with
-    128-token tiles it is a record (item, first list position, kept blocks, w) and an item longer
-    than the average load of a workgroup slot is cut into pieces by the rule in the header."""
+    128-token tiles it is a record (item, first list position, kept blocks, w) and an item that is
+    long against a CU's share of the work is cut into pieces by the rule in the header."""
     rows = B * H * nb
     n_split = 0
     for x in range(8):
@@ -172,7 +172,7 @@ def check_plan(counts, order, g, B, H, nb, block):
         want, run = [], 0
         for it in mine:
             c = int(counts[it])
-            P = split_pieces(c, total, g["slots"])
+            P = split_pieces(c, total)
             slot0 = -1
             if P > 1:
                 if run + P <= g["pmax"]:
@@ -223,8 +223,8 @@ def test_compaction_is_bit_exact_with_64_token_tiles():
 
 @pytest.mark.parametrize("D", [64, 128])
 def test_long_rows_are_split_into_pieces_and_merged(D):
-    """A few rows keep every tile while the rest keep few: the long rows exceed the average
-    load of a workgroup slot, are cut into pieces and combined by the last piece to finish.
+    """A few rows keep every tile while the rest keep few: the long rows are cut into pieces
+    and combined by the last piece to finish.
     The ragged tail block (kv_len inside it) is the last block of the last piece."""
     B, H, N, block, kv_len = 2, 8, 4608, 128, 4500
     nb = N // block
