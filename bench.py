@@ -6,7 +6,9 @@
 A step is one attention call of one DiT layer at the FLUX-like 1024^2 shape
 (B=1, H=24, N=4608, D=128, bf16): the dense entry point (Sparse-Attention action 0),
 the shape the headline metric is quoted on.  Inputs are synthetic (i.i.d. N(0,1)
-rounded to bf16), resident in HBM before the timed region.  The same run then times
+rounded to bf16), resident in HBM before the timed region (which is preceded by --ramp-ms
+of the same calls, so that the GPU clock has come up from idle, and by the W warm-up
+steps).  The same run then times
 the block-sparse entry point (mask compaction + attention) at each density of the
 workload and reports time / (effective density x dense time), and times the fp64
 CPU oracle on a bounded sample of rows of the same workload.
@@ -48,8 +50,12 @@ def measured_traffic(workload):
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--steps", type=int, default=1000)
+    ap.add_argument("--warmup", type=int, default=100)
+    ap.add_argument("--ramp-ms", type=float, default=150.0,
+                    help="before the warm-up steps, keep the GPU under the same load for this long: after "
+                         "idling, its clock takes some tens of milliseconds to come up (the first ~100 "
+                         "calls run ~13 %% slower)")
     ap.add_argument("--workload", default="flux_1024")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-sparse", action="store_true")
@@ -110,8 +116,13 @@ def main():
         return wall, float(np.mean(durs)), float(np.min(durs))
 
     # ---- the timed K steps: dense entry point
-    wall_ms, ev_mean, ev_min = time_calls(
-        lambda: ra.rapid_attn_dense(dq, dk, dv, do, w.kv_len), args.steps, args.warmup)
+    dense_call = lambda: ra.rapid_attn_dense(dq, dk, dv, do, w.kv_len)
+    t_ramp = time.perf_counter()
+    while (time.perf_counter() - t_ramp) * 1e3 < args.ramp_ms:
+        for _ in range(20):
+            dense_call()
+        torch.cuda.synchronize()
+    wall_ms, ev_mean, ev_min = time_calls(dense_call, args.steps, args.warmup)
     value = dense_flops / (wall_ms * 1e-3) / 1e12
     achieved = dense_flops / (ev_mean * 1e-3) / 1e12
 
@@ -173,7 +184,7 @@ def main():
             dm = torch.from_numpy(mask).cuda()
             s_wall, s_mean, s_min = time_calls(
                 lambda: ra.rapid_attn_block_sparse(dq, dk, dv, do, dm, w.block, w.kv_len, 0.0, ws),
-                max(20, args.steps // 2), max(5, args.warmup // 2))
+                max(20, min(200, args.steps // 2)), max(5, args.warmup // 2))
             sparse.append({"density_nominal": d, "density_effective": round(eff, 4),
                            "ms": round(s_mean, 5),
                            "eff_tflops": round(dense_flops * eff / (s_mean * 1e-3) / 1e12, 2),
