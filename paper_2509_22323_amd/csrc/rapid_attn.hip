@@ -105,22 +105,34 @@ __global__ __launch_bounds__(256) void compact_mask_kernel(
 constexpr int PLAN_MAX_NB = 8176;                // bins 0 .. nb fit the scan below
 constexpr int PLAN_BINS = 8192;                  // 8 bins per thread
 
-// Exclusive prefix sum of hist[0 .. PLAN_BINS) in place (1024 threads, thread t owns bins 8t..8t+7).
-__device__ __forceinline__ void plan_scan_bins(int* hist, int (*scan)[1024], int tid)
+constexpr int PLAN_CACHE = 4096;                 // counts of this many items are kept in LDS
+
+// Exclusive prefix sum of one value per thread over the 1024 threads of the block: a shuffle
+// scan inside each wavefront, then the 16 wavefront totals through LDS.  Two barriers.
+__device__ __forceinline__ int plan_block_scan(int v, int* wave_sum, int tid)
+{
+    const int lane = tid & 63, wv = tid >> 6;
+    int incl = v;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const int t = __shfl_up(incl, d, 64);
+        if (lane >= d) incl += t;
+    }
+    if (lane == 63) wave_sum[wv] = incl;
+    __syncthreads();
+    int before = 0;
+    for (int w = 0; w < wv; ++w) before += wave_sum[w];
+    __syncthreads();
+    return before + incl - v;
+}
+
+// Exclusive prefix sum of hist[0 .. PLAN_BINS) in place (thread t owns bins 8t..8t+7).
+__device__ __forceinline__ void plan_scan_bins(int* hist, int* wave_sum, int tid)
 {
     int own[8], sum = 0;
 #pragma unroll
     for (int j = 0; j < 8; ++j) { own[j] = hist[8 * tid + j]; sum += own[j]; }
-    scan[0][tid] = sum;
-    __syncthreads();
-    int cur = 0;
-    for (int d = 1; d < 1024; d <<= 1) {
-        const int v = scan[cur][tid] + (tid >= d ? scan[cur][tid - d] : 0);
-        scan[cur ^ 1][tid] = v;
-        cur ^= 1;
-        __syncthreads();
-    }
-    int run = scan[cur][tid] - sum;               // exclusive
+    int run = plan_block_scan(sum, wave_sum, tid);
 #pragma unroll
     for (int j = 0; j < 8; ++j) { hist[8 * tid + j] = run; run += own[j]; }
     __syncthreads();
@@ -131,7 +143,7 @@ __global__ __launch_bounds__(1024) void plan_kernel(const int32_t* __restrict__ 
                                                     int32_t* __restrict__ order)
 {
     __shared__ int hist[PLAN_BINS];              // by r = nb - count (r = 0: longest)
-    __shared__ int scan[2][1024];
+    __shared__ int wave_sum[16];
     const int x = blockIdx.x, tid = threadIdx.x;
     const int n_bh = (BH - x + XCDS - 1) / XCDS;  // (b,h) pairs with index % 8 == x
     const int n_items = n_bh > 0 ? n_bh * nb : 0;
@@ -142,11 +154,12 @@ __global__ __launch_bounds__(1024) void plan_kernel(const int32_t* __restrict__ 
         return;
     }
     for (int i = tid; i < chunk; i += 1024) out[i] = -1;
-    for (int r = tid; r < PLAN_BINS; r += 1024) hist[r] = 0;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) hist[8 * tid + j] = 0;
     __syncthreads();
     for (int i = tid; i < n_items; i += 1024) atomicAdd(&hist[nb - counts[item_of(i)]], 1);
     __syncthreads();
-    plan_scan_bins(hist, scan, tid);
+    plan_scan_bins(hist, wave_sum, tid);
     for (int i = tid; i < n_items; i += 1024) {
         const int item = item_of(i);
         out[atomicAdd(&hist[nb - counts[item]], 1)] = item;
@@ -191,13 +204,15 @@ __global__ __launch_bounds__(1024) void plan_split_kernel(const int32_t* __restr
                                                           int32_t* __restrict__ arrived)
 {
     __shared__ int hist[PLAN_BINS];              // by r = nb - length (r = 0: longest)
-    __shared__ int scan[2][1024];
+    __shared__ int ccache[PLAN_CACHE];           // counts of the first items, read once
+    __shared__ int wave_sum[16];
     __shared__ unsigned long long total;          // kept key-blocks of this XCD's items
     const int x = blockIdx.x, tid = threadIdx.x;
     const int n_bh = (BH - x + XCDS - 1) / XCDS;
     const int n_items = n_bh > 0 ? n_bh * nb : 0;
     PlanRec* out = recs + (size_t)x * cap;
     auto item_of = [&](int i) { return ((i / nb) * XCDS + x) * nb + i % nb; };
+    auto count_of = [&](int i) { return i < PLAN_CACHE ? ccache[i] : counts[item_of(i)]; };
     const PlanRec none = {-1, 0, 0, -1};
     for (int i = tid; i < pmax; i += 1024) arrived[(size_t)x * pmax + i] = 0;
     if (nb > PLAN_MAX_NB) {                       // no sort, no pieces: natural order
@@ -208,15 +223,22 @@ __global__ __launch_bounds__(1024) void plan_split_kernel(const int32_t* __restr
         }
         return;
     }
-    for (int i = tid; i < cap; i += 1024) out[i] = none;
-    for (int r = tid; r < PLAN_BINS; r += 1024) hist[r] = 0;
     if (tid == 0) total = 0ull;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) hist[8 * tid + j] = 0;
     __syncthreads();
     {
         unsigned long long mine = 0ull;
-        for (int i = tid; i < n_items; i += 1024) mine += (unsigned long long)counts[item_of(i)];
-        atomicAdd(&total, mine);
+        for (int i = tid; i < n_items; i += 1024) {
+            const int c = counts[item_of(i)];
+            if (i < PLAN_CACHE) ccache[i] = c;
+            mine += (unsigned long long)c;
+        }
+#pragma unroll
+        for (int d = 32; d >= 1; d >>= 1) mine += __shfl_down(mine, d, 64);
+        if ((tid & 63) == 0) atomicAdd(&total, mine);
     }
+    for (int i = tid; i < cap; i += 1024) out[i] = none;
     __syncthreads();
     const unsigned long long tot = total;
     // partial-result slots in item order: thread t owns the items [lo, hi)
@@ -225,20 +247,10 @@ __global__ __launch_bounds__(1024) void plan_split_kernel(const int32_t* __restr
     const int hi = lo + per < n_items ? lo + per : n_items;
     int mine = 0;
     for (int i = lo; i < hi; ++i) {
-        const int P = split_pieces(counts[item_of(i)], tot);
+        const int P = split_pieces(count_of(i), tot);
         if (P > 1) mine += P;
     }
-    scan[0][tid] = mine;
-    __syncthreads();
-    int cur = 0;
-    for (int d = 1; d < 1024; d <<= 1) {
-        const int v = scan[cur][tid] + (tid >= d ? scan[cur][tid - d] : 0);
-        scan[cur ^ 1][tid] = v;
-        cur ^= 1;
-        __syncthreads();
-    }
-    const int first_slot = scan[cur][tid] - mine;
-    __syncthreads();
+    const int first_slot = plan_block_scan(mine, wave_sum, tid);
     // pieces of item i: P (1 = whole) and the first partial slot
     auto pieces_of = [&](int c, int& run, int& P, int& slot0) {
         const int want = split_pieces(c, tot);
@@ -252,19 +264,19 @@ __global__ __launch_bounds__(1024) void plan_split_kernel(const int32_t* __restr
     {
         int run = first_slot;
         for (int i = lo; i < hi; ++i) {
-            const int c = counts[item_of(i)];
+            const int c = count_of(i);
             int P, slot0;
             pieces_of(c, run, P, slot0);
             for (int k = 0; k < P; ++k) atomicAdd(&hist[nb - (c * (k + 1) / P - c * k / P)], 1);
         }
     }
     __syncthreads();
-    plan_scan_bins(hist, scan, tid);
+    plan_scan_bins(hist, wave_sum, tid);
     {
         int run = first_slot;
         for (int i = lo; i < hi; ++i) {
             const int item = item_of(i);
-            const int c = counts[item];
+            const int c = count_of(i);
             int P, slot0;
             pieces_of(c, run, P, slot0);
             for (int k = 0; k < P; ++k) {
