@@ -599,6 +599,31 @@ __device__ __forceinline__ void load_q(const __bf16* __restrict__ Q, int qrow, b
     }
 }
 
+// The same fragments requested by explicit assembly: the compiler then places no waits of
+// its own for them (it cannot count the tile copies issued around them and would wait for
+// everything); the caller waits with wait_vmcnt and then passes the fragments through
+// q_arrived so that their uses stay behind that wait.  Rows that are not valid read row 0
+// of the (sample, head) and are zeroed afterwards.
+template <int D>
+__device__ __forceinline__ void load_q_async(const __bf16* __restrict__ Q, int qrow, bool qvalid, int h, u32x4 (&raw)[D / 16])
+{
+    const __bf16* src = Q + (size_t)(qvalid ? qrow : 0) * D + 8 * h;
+#pragma unroll
+    for (int t = 0; t < D / 16; ++t)
+        asm volatile("global_load_dwordx4 %0, %1, off offset:%2" : "=v"(raw[t]) : "v"(src), "i"(32 * t));
+}
+
+template <int D>
+__device__ __forceinline__ void q_arrived(u32x4 (&raw)[D / 16], bool qvalid, bf16x8 (&qf)[D / 16])
+{
+#pragma unroll
+    for (int t = 0; t < D / 16; ++t) {
+        asm volatile("" : "+v"(raw[t]));
+        const u32x4 zero = {0u, 0u, 0u, 0u};
+        qf[t] = __builtin_bit_cast(bf16x8, qvalid ? raw[t] : zero);
+    }
+}
+
 // s_waitcnt with only the vector-memory counter constrained (gfx9 encoding: vmcnt in
 // bits 3:0 and 15:14, expcnt 6:4 and lgkmcnt 11:8 left at their maxima)
 template <int VM>
@@ -1039,19 +1064,23 @@ __global__ __launch_bounds__(256, (D == 64 ? 4 : 2)) void attn_sparse_sg_kernel(
     int kn2 = (2 < T) ? key_of(2) : 0;
     int kn3 = (3 < T) ? key_of(3) : 0;
 
+    // Q and K_0 first: S_0 needs only these; V_0 and K_1 land while it is computed.
+    u32x4 qraw[KS];
+    load_q_async<D>(Q, qrow, qvalid, h, qraw);
     issue_tile<D, NW, false>(K, key0, kv_len, k_stage(0), wave, lane);
     issue_tile<D, NW, true>(V, key0, kv_len, v_stage(0), wave, lane);
     if (1 < T) issue_tile<D, NW, false>(K, kn1, kv_len, k_stage(1), wave, lane);
 
-    bf16x8 qf[KS];
-    load_q<D>(Q, qrow, qvalid, h, qf);
     SoftmaxState sm;
     sm.m = -INFINITY;
     sm.l = 0.f;
     const float tau = 8.0f / p.c;
     const int tr_row = (lane & 15) >> 2;
     const int tr_col = ((lane & 3) << 2) + (((lane >> 4) & 1) << 4);
-    wait_vmcnt<0>();
+    if (1 < T) wait_vmcnt<2 * LPT>();
+    else wait_vmcnt<LPT>();
+    bf16x8 qf[KS];
+    q_arrived<D>(qraw, qvalid, qf);
     __syncthreads();
 
     TileCtx<D> ctx;
@@ -1061,6 +1090,8 @@ __global__ __launch_bounds__(256, (D == 64 ? 4 : 2)) void attn_sparse_sg_kernel(
     items_prefetch<D, TI::NPV, TI::NI>(ctx);
     items_run<D, TI::NPV, TI::NI>(ctx, pb, qf, acc, st);   // S_0
     mask_tail(st, key0, kv_len, h);
+    if (1 < T) wait_vmcnt<LPT>();                 // V_0 landed (K_1 may still be on its way)
+    else wait_vmcnt<0>();
 
     for (int j = 0; j < T; ++j) {
         phase_barrier();                          // A(j-1) (or S_0) finished by every wavefront; V_j landed
