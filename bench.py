@@ -60,6 +60,7 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-sparse", action="store_true")
     ap.add_argument("--no-mfma-probe", action="store_true")
+    ap.add_argument("--no-cache-ops", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain device copy of the Q tensor (known size) so that HBM "
@@ -190,6 +191,42 @@ def main():
                            "eff_tflops": round(dense_flops * eff / (s_mean * 1e-3) / 1e12, 2),
                            "time_over_density_x_dense": round(s_mean / (eff * ev_mean), 3)})
         out["sparse"] = sparse
+
+    # ---- Cache-Reuse residual operations (O = X + Delta, Delta = G(X) - X): streaming kernels,
+    # bound by HBM (6 bytes per element).  Two sizes: the latent of one image at this workload's
+    # resolution (launch-latency bound) and one layer's hidden states (joint tokens x 3072 channels).
+    if not args.no_cache_ops:
+        cache = []
+        for label, elems in (("latent of one image: 4096 tokens x 64 channels", 4096 * 64),
+                             (f"hidden states of one layer: {w.N} tokens x 3072 channels", w.N * 3072)):
+            # rotate over enough tensor sets to exceed the 256 MB memory-side cache, so that the
+            # large case streams from HBM and not from that cache
+            sets = max(1, min(8, int(600e6 // (6 * elems))))
+            g = torch.Generator(device="cuda")
+            g.manual_seed(3)
+            xs = [torch.randn(1, elems, device="cuda", generator=g).bfloat16() for _ in range(sets)]
+            ds = [torch.randn(1, elems, device="cuda", generator=g).bfloat16() for _ in range(sets)]
+            os_ = [torch.empty_like(x) for x in xs]
+            turn = [0]
+
+            def reuse():
+                i = turn[0] = (turn[0] + 1) % sets
+                ra.rapid_cache_reuse(xs[i], ds[i], os_[i])
+
+            def store():
+                i = turn[0] = (turn[0] + 1) % sets
+                ra.rapid_cache_store(os_[i], xs[i], ds[i])
+
+            _, r_mean, r_min = time_calls(reuse, 200, 20)
+            _, s_mean, s_min = time_calls(store, 200, 20)
+            gbs = 6.0 * elems / (r_mean * 1e-3) / 1e9
+            cache.append({"tensor": label, "elements": elems, "tensor_sets_rotated": sets,
+                          "reuse_ms": round(r_mean, 5), "store_ms": round(s_mean, 5),
+                          "roofline": {"bound": "hbm", "kernel": "cache_residual_kernel", "achieved": round(gbs, 1),
+                                       "peak": 8000.0, "unit": "GB/s", "frac": round(gbs / 8000.0, 4),
+                                       "algorithmic_bytes": 6 * elems}})
+            del xs, ds, os_
+        out["cache_reuse"] = cache
 
     # ---- the oracle on this machine's host cores, bounded sample of rows of the same workload
     if not args.no_cpu_baseline:

@@ -58,12 +58,14 @@ def f64_to_bf16(x) -> np.ndarray:
 
 def cache_store(o_bits, x_bits) -> np.ndarray:
     """Delta = G(X) - X: the residual that a cache-updating step leaves behind."""
-    return f64_to_bf16(bf16_to_f64(o_bits) - bf16_to_f64(x_bits))
+    with np.errstate(invalid="ignore"):                   # inf - inf is a NaN, as it should be
+        return f64_to_bf16(bf16_to_f64(o_bits) - bf16_to_f64(x_bits))
 
 
 def cache_reuse(x_bits, delta_bits) -> np.ndarray:
     """O = X + Delta: the output of a step that reuses the cached residual."""
-    return f64_to_bf16(bf16_to_f64(x_bits) + bf16_to_f64(delta_bits))
+    with np.errstate(invalid="ignore"):
+        return f64_to_bf16(bf16_to_f64(x_bits) + bf16_to_f64(delta_bits))
 
 
 def cache_reuse_batch(x_bits, delta_bits, out_bits, flags) -> np.ndarray:

@@ -11,10 +11,15 @@ from .binding import (  # noqa: F401
     rapid_attn_status_string,
     rapid_attn_version,
     rapid_attn_workspace_bytes,
+    rapid_cache_reuse,
+    rapid_cache_store,
+    rapid_equivalent_steps,
+    rapid_reward,
     STATUS,
 )
 
 __all__ = [
     "RapidAttnError", "library", "library_path", "rapid_attn_block_sparse", "rapid_attn_dense",
-    "rapid_attn_status_string", "rapid_attn_version", "rapid_attn_workspace_bytes", "STATUS",
+    "rapid_attn_status_string", "rapid_attn_version", "rapid_attn_workspace_bytes", "rapid_cache_reuse",
+    "rapid_cache_store", "rapid_equivalent_steps", "rapid_reward", "STATUS",
 ]

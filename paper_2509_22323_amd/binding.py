@@ -20,6 +20,7 @@ STATUS = {
 
 EXPORTS = ("rapid_attn_dense", "rapid_attn_block_sparse", "rapid_attn_workspace_bytes",
            "rapid_attn_status_string", "rapid_attn_version")
+CACHE_EXPORTS = ("rapid_cache_store", "rapid_cache_reuse", "rapid_equivalent_steps", "rapid_reward")
 
 
 class RapidAttnError(RuntimeError):
@@ -64,6 +65,15 @@ def library():
     lib.rapid_attn_status_string.restype = ctypes.c_char_p
     lib.rapid_attn_version.argtypes = []
     lib.rapid_attn_version.restype = ci
+    cd, dp = ctypes.c_double, ctypes.POINTER(ctypes.c_double)
+    lib.rapid_cache_store.argtypes = [vp, vp, vp, ci, sz, vp, vp]
+    lib.rapid_cache_store.restype = ci
+    lib.rapid_cache_reuse.argtypes = [vp, vp, vp, ci, sz, vp, vp]
+    lib.rapid_cache_reuse.restype = ci
+    lib.rapid_equivalent_steps.argtypes = [dp, dp, ci, dp]
+    lib.rapid_equivalent_steps.restype = ci
+    lib.rapid_reward.argtypes = [cd, cd, cd, cd, ci]
+    lib.rapid_reward.restype = cd
     _lib = lib
     return lib
 
@@ -133,3 +143,56 @@ def rapid_attn_block_sparse(q, k, v, o, mask, block, kv_len=None, scale=0.0, wor
         q.data_ptr(), k.data_ptr(), v.data_ptr(), o.data_ptr(), B, H, N, D, int(block),
         mask.data_ptr(), kv_len, float(scale), workspace.data_ptr(), ws_bytes, _stream(q)))
     return o
+
+
+# ---------------------------------------------------------------- Cache-Reuse residual operations
+def _residual_args(a, b, out, sample_flags):
+    import torch
+    for name, t in (("first input", a), ("second input", b), ("output", out)):
+        if not (isinstance(t, torch.Tensor) and t.is_cuda and t.dtype == torch.bfloat16 and t.is_contiguous()
+                and t.dim() >= 1):
+            raise TypeError(f"{name} must be a contiguous CUDA bfloat16 tensor [B, ...]")
+        if t.shape != a.shape or t.device != a.device:
+            raise ValueError(f"{name}: shape/device differs")
+    B = int(a.shape[0])
+    per_sample = a.numel() // B if B > 0 else 0
+    flags = None
+    if sample_flags is not None:
+        if not (isinstance(sample_flags, torch.Tensor) and sample_flags.is_cuda and sample_flags.dtype == torch.uint8
+                and sample_flags.is_contiguous() and sample_flags.numel() == B and sample_flags.device == a.device):
+            raise TypeError("sample_flags must be a contiguous CUDA uint8 tensor [B]")
+        flags = sample_flags.data_ptr()
+    return B, per_sample, flags
+
+
+def rapid_cache_store(gen_out, x, delta, sample_flags=None):
+    """delta <- gen_out - x (the residual a cache-updating step keeps), per flagged sample."""
+    B, per_sample, flags = _residual_args(gen_out, x, delta, sample_flags)
+    _check(library().rapid_cache_store(gen_out.data_ptr(), x.data_ptr(), delta.data_ptr(), B, per_sample, flags,
+                                       _stream(x)))
+    return delta
+
+
+def rapid_cache_reuse(x, delta, out, sample_flags=None):
+    """out <- x + delta (the output of a step that reuses the cache), per flagged sample."""
+    B, per_sample, flags = _residual_args(x, delta, out, sample_flags)
+    _check(library().rapid_cache_reuse(x.data_ptr(), delta.data_ptr(), out.data_ptr(), B, per_sample, flags,
+                                       _stream(x)))
+    return out
+
+
+def rapid_equivalent_steps(c_cache, c_sparse):
+    """(K exact, K rounded) for the per-step cost reductions (host arithmetic in the library)."""
+    n = len(c_cache)
+    if len(c_sparse) != n:
+        raise ValueError("c_cache and c_sparse differ in length")
+    arr = ctypes.c_double * max(n, 1)
+    exact = ctypes.c_double(0.0)
+    k = library().rapid_equivalent_steps(arr(*c_cache), arr(*c_sparse), n, ctypes.byref(exact))
+    if k < 0:
+        _check(k)
+    return exact.value, k
+
+
+def rapid_reward(q, d, K, lam=0.97, omega=1.0):
+    return library().rapid_reward(float(q), float(d), float(omega), float(lam), int(K))
