@@ -61,6 +61,7 @@ def parse():
     ap.add_argument("--no-sparse", action="store_true")
     ap.add_argument("--no-mfma-probe", action="store_true")
     ap.add_argument("--no-cache-ops", action="store_true")
+    ap.add_argument("--no-joint", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain device copy of the Q tensor (known size) so that HBM "
@@ -191,6 +192,24 @@ def main():
                            "eff_tflops": round(dense_flops * eff / (s_mean * 1e-3) / 1e12, 2),
                            "time_over_density_x_dense": round(s_mean / (eff * ev_mean), 3)})
         out["sparse"] = sparse
+
+    # ---- the same dense call on tensors as an MM-DiT block holds them: image and text stream in
+    # separate fused-QKV tensors [B, n, 3, H, D], outputs [B, n, H, D] (no concatenated copy)
+    n_txt = 512 if w.N > 1024 else 0
+    if not args.no_joint and (w.N - n_txt) % 128 == 0:
+        segs = []
+        for a, b in ((0, w.N - n_txt), (w.N - n_txt, w.N)) if n_txt else ((0, w.N),):
+            fused = torch.empty(w.B, b - a, 3, w.H, w.D, dtype=torch.bfloat16, device="cuda")
+            for j, x in enumerate((dq, dk, dv)):
+                fused[:, :, j] = x[:, :, a:b].permute(0, 2, 1, 3)
+            o_seg = torch.empty(w.B, b - a, w.H, w.D, dtype=torch.bfloat16, device="cuda")
+            segs.append(tuple(fused[:, :, j].permute(0, 2, 1, 3) for j in range(3)) + (o_seg.permute(0, 2, 1, 3),))
+        _, j_mean, j_min = time_calls(lambda: ra.rapid_attn_joint(segs, None, w.block, kv_len=w.kv_len),
+                                      max(20, min(200, args.steps // 2)), max(5, args.warmup // 2))
+        out["joint_layout"] = {"layout": f"{len(segs)} segment(s), fused [B,n,3,H,D] inputs, [B,n,H,D] outputs",
+                               "ms": round(j_mean, 5), "tflops": round(dense_flops / (j_mean * 1e-3) / 1e12, 2),
+                               "time_over_contiguous": round(j_mean / ev_mean, 3)}
+        del segs
 
     # ---- Cache-Reuse residual operations (O = X + Delta, Delta = G(X) - X): streaming kernels,
     # bound by HBM (6 bytes per element).  Two sizes: the latent of one image at this workload's

@@ -127,6 +127,56 @@ RAPID_API int rapid_attn_block_sparse(const void* q, const void* k, const void* 
  * shape is invalid or unsupported.  Pure host arithmetic. */
 RAPID_API size_t rapid_attn_workspace_bytes(int B, int H, int N, int D, int block);
 
+/*
+ * The same attention on tensors as an MM-DiT block holds them (Sec. 3.1: the text
+ * and the image stream are separate tensors, joined only for attention): the
+ * joint sequence is given as one or two token segments, each with its own
+ * Q/K/V/O tensors and strides, so no concatenated or transposed copy is needed.
+ * Token t of the joint sequence is row t of segment 0 if t < segments[0].n,
+ * else row t - segments[0].n of segment 1; N = sum of the n.
+ *   q,k,v,o      device, bf16; element (b, h, r, d) of a tensor lies at
+ *                ptr + b*stride_b + h*stride_h + r*stride_n + d  (elements; the
+ *                D elements of a row are contiguous).  in_stride_* address
+ *                q, k and v, out_stride_* address o.  [B,n,H,D] tensors have
+ *                stride_b = n*H*D, stride_h = D, stride_n = H*D; a fused
+ *                [B,n,3,H,D] projection has in_stride_n = 3*H*D.
+ *   constraints  pointers 16-byte aligned, strides multiples of 8 elements,
+ *                D <= stride_n <= 2^23; with two segments segments[0].n is a
+ *                multiple of 128 (no 64-key tile and no 128-query block lies in
+ *                both tensors) and stride_h, stride_n are the same in both.
+ */
+typedef struct rapid_attn_segment {
+    const void* q;
+    const void* k;
+    const void* v;
+    void* o;
+    int n;                                            /* tokens in this segment */
+    long long in_stride_b, in_stride_h, in_stride_n;  /* of q, k, v */
+    long long out_stride_b, out_stride_h, out_stride_n;
+} rapid_attn_segment;
+
+/*
+ * Joint attention over the segments (dense when mask is NULL, else block-sparse).
+ *   segments     HOST array of n_segments (1 or 2) descriptors, read during the call
+ *   block, mask  as rapid_attn_block_sparse, except that N need not be a multiple
+ *                of block: nb = ceil(N/block) and the last block ends at N.
+ *                mask NULL = dense (block ignored)
+ *   kv_len       valid tokens for every sample, 1..N; 0 selects N
+ *   kv_lens      device, int32 [B], or NULL: per-sample valid tokens (prompts of
+ *                different length in one batch), each clamped to 0..N; replaces
+ *                kv_len when given.  A sample with 0 valid tokens outputs zeros.
+ *   workspace    sparse only: at least rapid_attn_joint_workspace_bytes(B,H,N,D,block)
+ *   other arguments and all semantics as above.
+ */
+RAPID_API int rapid_attn_joint(const rapid_attn_segment* segments, int n_segments,
+                     int B, int H, int D, int block, const unsigned char* mask,
+                     int kv_len, const int* kv_lens, float scale,
+                     void* workspace, size_t workspace_bytes, void* stream);
+
+/* Workspace bytes of the sparse form of rapid_attn_joint (N = total tokens, any
+ * positive count); 0 if the shape is invalid or unsupported. */
+RAPID_API size_t rapid_attn_joint_workspace_bytes(int B, int H, int N, int D, int block);
+
 /* Static, NUL-terminated description of a status code.  Never NULL. */
 RAPID_API const char* rapid_attn_status_string(int status);
 

@@ -19,7 +19,17 @@ STATUS = {
 }
 
 EXPORTS = ("rapid_attn_dense", "rapid_attn_block_sparse", "rapid_attn_workspace_bytes",
+           "rapid_attn_joint", "rapid_attn_joint_workspace_bytes",
            "rapid_attn_status_string", "rapid_attn_version")
+
+
+class Segment(ctypes.Structure):
+    """rapid_attn_segment of include/rapid_attn.h."""
+    _fields_ = [("q", ctypes.c_void_p), ("k", ctypes.c_void_p), ("v", ctypes.c_void_p), ("o", ctypes.c_void_p),
+                ("n", ctypes.c_int),
+                ("in_stride_b", ctypes.c_longlong), ("in_stride_h", ctypes.c_longlong), ("in_stride_n", ctypes.c_longlong),
+                ("out_stride_b", ctypes.c_longlong), ("out_stride_h", ctypes.c_longlong),
+                ("out_stride_n", ctypes.c_longlong)]
 CACHE_EXPORTS = ("rapid_cache_store", "rapid_cache_reuse", "rapid_equivalent_steps", "rapid_reward")
 
 
@@ -61,6 +71,10 @@ def library():
     lib.rapid_attn_block_sparse.restype = ci
     lib.rapid_attn_workspace_bytes.argtypes = [ci, ci, ci, ci, ci]
     lib.rapid_attn_workspace_bytes.restype = sz
+    lib.rapid_attn_joint.argtypes = [ctypes.POINTER(Segment), ci, ci, ci, ci, ci, vp, ci, vp, cf, vp, sz, vp]
+    lib.rapid_attn_joint.restype = ci
+    lib.rapid_attn_joint_workspace_bytes.argtypes = [ci, ci, ci, ci, ci]
+    lib.rapid_attn_joint_workspace_bytes.restype = sz
     lib.rapid_attn_status_string.argtypes = [ci]
     lib.rapid_attn_status_string.restype = ctypes.c_char_p
     lib.rapid_attn_version.argtypes = []
@@ -143,6 +157,64 @@ def rapid_attn_block_sparse(q, k, v, o, mask, block, kv_len=None, scale=0.0, wor
         q.data_ptr(), k.data_ptr(), v.data_ptr(), o.data_ptr(), B, H, N, D, int(block),
         mask.data_ptr(), kv_len, float(scale), workspace.data_ptr(), ws_bytes, _stream(q)))
     return o
+
+
+def rapid_attn_joint_workspace_bytes(B: int, H: int, N: int, D: int, block: int) -> int:
+    return int(library().rapid_attn_joint_workspace_bytes(B, H, N, D, block))
+
+
+def rapid_attn_joint(segments, mask=None, block=128, kv_len=None, kv_lens=None, scale=0.0, workspace=None):
+    """Joint attention over one or two token segments.  `segments`: sequence of (q, k, v, o),
+    each a CUDA bf16 tensor indexed [B, H, n, D] with a contiguous last dimension and any other
+    strides (a permuted view of a [B, n, H, D] or fused [B, n, 3, H, D] tensor is fine); q, k, v
+    of a segment share their strides.  mask None = dense.  kv_lens: CUDA int32 [B] or None."""
+    import torch
+    if len(segments) not in (1, 2):
+        raise ValueError("one or two segments")
+    descr = (Segment * len(segments))()
+    B = H = D = None
+    N = 0
+    for i, (q, k, v, o) in enumerate(segments):
+        for name, t in (("q", q), ("k", k), ("v", v), ("o", o)):
+            if not (isinstance(t, torch.Tensor) and t.is_cuda and t.dtype == torch.bfloat16 and t.dim() == 4
+                    and t.stride(3) == 1):
+                raise TypeError(f"segment {i}: {name} must be a CUDA bfloat16 tensor [B,H,n,D] with contiguous D")
+            if t.shape != q.shape or t.device != q.device:
+                raise ValueError(f"segment {i}: {name} shape/device differs from q")
+        if k.stride() != q.stride() or v.stride() != q.stride():
+            raise ValueError(f"segment {i}: q, k, v must share their strides")
+        if B is None:
+            B, H, _, D = (int(x) for x in q.shape)
+        elif (int(q.shape[0]), int(q.shape[1]), int(q.shape[3])) != (B, H, D):
+            raise ValueError("segments differ in B, H or D")
+        g = descr[i]
+        g.q, g.k, g.v, g.o, g.n = q.data_ptr(), k.data_ptr(), v.data_ptr(), o.data_ptr(), int(q.shape[2])
+        g.in_stride_b, g.in_stride_h, g.in_stride_n = q.stride(0), q.stride(1), q.stride(2)
+        g.out_stride_b, g.out_stride_h, g.out_stride_n = o.stride(0), o.stride(1), o.stride(2)
+        N += int(q.shape[2])
+    q0 = segments[0][0]
+    mask_ptr, ws_ptr, ws_bytes = None, None, 0
+    if mask is not None:
+        if not (isinstance(mask, torch.Tensor) and mask.is_cuda and mask.dtype == torch.uint8
+                and mask.is_contiguous() and mask.device == q0.device):
+            raise TypeError("mask must be a contiguous CUDA uint8 tensor")
+        nb = -(-N // int(block)) if block > 0 else 0
+        if tuple(mask.shape) != (B, H, nb, nb):
+            raise ValueError(f"mask shape {tuple(mask.shape)} != {(B, H, nb, nb)}")
+        if workspace is None:
+            workspace = torch.empty(max(rapid_attn_joint_workspace_bytes(B, H, N, D, int(block)), 16),
+                                    dtype=torch.uint8, device=q0.device)
+        mask_ptr, ws_ptr, ws_bytes = mask.data_ptr(), workspace.data_ptr(), workspace.numel() * workspace.element_size()
+    lens_ptr = None
+    if kv_lens is not None:
+        if not (isinstance(kv_lens, torch.Tensor) and kv_lens.is_cuda and kv_lens.dtype == torch.int32
+                and kv_lens.is_contiguous() and kv_lens.numel() == B and kv_lens.device == q0.device):
+            raise TypeError("kv_lens must be a contiguous CUDA int32 tensor [B]")
+        lens_ptr = kv_lens.data_ptr()
+    _check(library().rapid_attn_joint(descr, len(segments), B, H, D, int(block), mask_ptr,
+                                      0 if kv_len is None else int(kv_len), lens_ptr, float(scale),
+                                      ws_ptr, ws_bytes, _stream(q0)))
+    return [seg[3] for seg in segments]
 
 
 # ---------------------------------------------------------------- Cache-Reuse residual operations

@@ -50,11 +50,41 @@ constexpr float LOG2E = 1.44269504088896340736f;
 
 #define LDS_PTR(T, p) ((__attribute__((address_space(3))) T*)(p))
 
+// A [B, H, tokens, D] tensor handed over as one or two token segments: token t < n0 is row t
+// of segment 0, any other token is row t - n0 of segment 1 (MM-DiT keeps the image and the
+// text stream in separate tensors and joins them only for attention).  Strides in elements,
+// D contiguous; head and token strides are common to both segments.
+struct SegTensor {
+    const __bf16* seg0;
+    const __bf16* seg1;      // null when there is one segment
+    long long sb0, sb1;      // batch strides
+    long long sh, sn;        // head stride, token stride
+};
+
+// The token rows of one (sample, head): row r starts at (r < n0 ? base0 : base1) + r * row_bytes
+// (base1 is biased by -n0 rows so that both segments are indexed by the joint token number).
+struct Rows {
+    const char* base0;
+    const char* base1;
+    int n0;
+    unsigned row_bytes;
+    __device__ __forceinline__ const char* row(int r) const { return (r < n0 ? base0 : base1) + (size_t)r * row_bytes; }
+};
+
+__device__ __forceinline__ Rows rows_of(const SegTensor& t, int b, int h, int n0)
+{
+    Rows r;
+    r.base0 = (const char*)(t.seg0 + (size_t)b * t.sb0 + (size_t)h * t.sh);
+    r.base1 = t.seg1 ? (const char*)(t.seg1 + (size_t)b * t.sb1 + (size_t)h * t.sh) - (size_t)n0 * t.sn * 2 : r.base0;
+    r.n0 = n0;
+    r.row_bytes = (unsigned)(t.sn * 2);
+    return r;
+}
+
 struct AttnParams {
-    const __bf16* q;
-    const __bf16* k;
-    const __bf16* v;
-    __bf16* o;
+    SegTensor q, k, v, o;
+    const int32_t* kv_lens;  // per-sample valid tokens (device, [B]) or null: kv_len for all
+    int n0;                  // tokens in the first segment (N when there is one)
     const int32_t* counts;   // sparse: kept key-blocks per (b,h,query-block); dense: null
     const int32_t* order;    // sparse: launch plan (64-token tiles: item ids; 128-token tiles: PlanRec records)
     const int32_t* index;    // sparse: kept key-block lists, nb per row
@@ -76,11 +106,16 @@ struct AttnParams {
 // ---------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void compact_mask_kernel(
     const unsigned char* __restrict__ mask, int rows, int nb, int block, int kv_len,
+    const int32_t* __restrict__ kv_lens, int rows_per_sample, int N,
     int32_t* __restrict__ counts, int32_t* __restrict__ index)
 {
     const int lane = threadIdx.x & 63;
     const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
     if (row >= rows) return;
+    if (kv_lens != nullptr) {
+        kv_len = kv_lens[row / rows_per_sample];
+        kv_len = kv_len < 0 ? 0 : (kv_len > N ? N : kv_len);
+    }
     const unsigned char* mrow = mask + (size_t)row * nb;
     int32_t* irow = index + (size_t)row * nb;
     int base = 0;
@@ -319,7 +354,7 @@ struct Geo {
 // beyond kv_len are replaced by row kv_len-1 (finite data; their probabilities are exactly
 // 0, and their scores are overwritten with -inf, so they never contribute).
 template <int D, int NW, bool IS_V>
-__device__ __forceinline__ void issue_tile(const __bf16* __restrict__ src, int key0, int kv_len,
+__device__ __forceinline__ void issue_tile(const Rows& src, int key0, int kv_len,
                                            char* lds, int wave, int lane)
 {
     typedef Geo<D> G;
@@ -331,13 +366,13 @@ __device__ __forceinline__ void issue_tile(const __bf16* __restrict__ src, int k
     if (key0 + KT <= kv_len) {
         // whole tile valid: scalar tile base + a per-lane byte offset that does not depend
         // on the tile (no vector arithmetic per copy)
-        const char* tile = (const char*)(src + (size_t)key0 * D);
+        const char* tile = src.row(key0);                  // a tile never straddles the segments
 #pragma unroll
         for (int i = 0; i < PER_WAVE; ++i) {
             const int ld = wave * PER_WAVE + i;             // wave-uniform
             const int row = ld * G::ROWS_PER_LOAD + lane / G::CPR;
             const int logical = (lane % G::CPR) ^ (IS_V ? G::swz_v(row) : G::swz_k(row));
-            const unsigned off = (unsigned)(row * D + logical * 8) * 2u;
+            const unsigned off = (unsigned)row * src.row_bytes + (unsigned)logical * 16u;
             const unsigned dst = (unsigned)(size_t)LDS_PTR(char, lds + ld * 1024);
             asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(dst), "v"(off), "s"(tile));
         }
@@ -349,7 +384,7 @@ __device__ __forceinline__ void issue_tile(const __bf16* __restrict__ src, int k
             const int logical = (lane % G::CPR) ^ (IS_V ? G::swz_v(row) : G::swz_k(row));
             int grow = key0 + row;
             grow = grow < kv_len ? grow : kv_len - 1;
-            const __bf16* g = src + (size_t)grow * D + logical * 8;
+            const char* g = (key0 < src.n0 ? src.base0 : src.base1) + (size_t)grow * src.row_bytes + logical * 16;
             const unsigned dst = (unsigned)(size_t)LDS_PTR(char, lds + ld * 1024);
             asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(dst), "v"(g));
         }
@@ -562,7 +597,7 @@ __device__ __forceinline__ void softmax_tile(const f32x16 (&st)[2], f32x16 (&acc
 // Epilogue: O = acc / l as bf16.  Register 4j+r of block db holds d = 32 db + 8 j + 4 h + r
 // of this lane's query; rows at or beyond kv_len and rows without any kept key become 0.
 template <int D>
-__device__ __forceinline__ void write_output(__bf16* __restrict__ O, const f32x16 (&acc)[D / 32], float l_part,
+__device__ __forceinline__ void write_output(const Rows& O, const f32x16 (&acc)[D / 32], float l_part,
                                              int qrow, bool qvalid, int N, int h)
 {
     float l_run = l_part;
@@ -572,6 +607,7 @@ __device__ __forceinline__ void write_output(__bf16* __restrict__ O, const f32x1
     }
     const float inv = (qvalid && l_run > 0.f) ? 1.0f / l_run : 0.f;
     if (qrow < N) {
+        __bf16* orow = (__bf16*)const_cast<char*>(O.row(qrow));
 #pragma unroll
         for (int db = 0; db < D / 32; ++db)
 #pragma unroll
@@ -582,19 +618,20 @@ __device__ __forceinline__ void write_output(__bf16* __restrict__ O, const f32x1
                     const float x = acc[db][4 * j + r] * inv;
                     ov[r] = (__bf16)((inv != 0.f) ? x : 0.f);
                 }
-                *(bf16x4*)(O + (size_t)qrow * D + 32 * db + 8 * j + 4 * h) = ov;
+                *(bf16x4*)(orow + 32 * db + 8 * j + 4 * h) = ov;
             }
     }
 }
 
 // Q^T fragments (B operand of S^T = K Q^T): lane (n, h) holds Q[qrow][16t + 8h .. +8].
 template <int D>
-__device__ __forceinline__ void load_q(const __bf16* __restrict__ Q, int qrow, bool qvalid, int h, bf16x8 (&qf)[D / 16])
+__device__ __forceinline__ void load_q(const Rows& Q, int qrow, bool qvalid, int h, bf16x8 (&qf)[D / 16])
 {
+    const __bf16* qr = (const __bf16*)Q.row(qvalid ? qrow : 0);
 #pragma unroll
     for (int t = 0; t < D / 16; ++t) {
         u32x4 raw = {0u, 0u, 0u, 0u};
-        if (qvalid) raw = *(const u32x4*)(Q + (size_t)qrow * D + 16 * t + 8 * h);
+        if (qvalid) raw = *(const u32x4*)(qr + 16 * t + 8 * h);
         qf[t] = __builtin_bit_cast(bf16x8, raw);
     }
 }
@@ -605,9 +642,9 @@ __device__ __forceinline__ void load_q(const __bf16* __restrict__ Q, int qrow, b
 // q_arrived so that their uses stay behind that wait.  Rows that are not valid read row 0
 // of the (sample, head) and are zeroed afterwards.
 template <int D>
-__device__ __forceinline__ void load_q_async(const __bf16* __restrict__ Q, int qrow, bool qvalid, int h, u32x4 (&raw)[D / 16])
+__device__ __forceinline__ void load_q_async(const Rows& Q, int qrow, bool qvalid, int h, u32x4 (&raw)[D / 16])
 {
-    const __bf16* src = Q + (size_t)(qvalid ? qrow : 0) * D + 8 * h;
+    const __bf16* src = (const __bf16*)Q.row(qvalid ? qrow : 0) + 8 * h;
 #pragma unroll
     for (int t = 0; t < D / 16; ++t)
         asm volatile("global_load_dwordx4 %0, %1, off offset:%2" : "=v"(raw[t]) : "v"(src), "i"(32 * t));
@@ -690,15 +727,26 @@ __device__ __forceinline__ void dense_item(const AttnParams& p, char* lds, int b
     const int group = wave >> 2;
     const int n = lane & 31;                      // query within the wavefront / MFMA column
     const int h = lane >> 5;                      // lane half
-    const int kv_len = p.kv_len;
+    int kv_len = p.kv_len;
+    if (p.kv_lens != nullptr) {                   // per-sample length, clamped to 0..N
+        kv_len = ((const __attribute__((address_space(4))) int32_t*)p.kv_lens)[bh / p.H];
+        kv_len = kv_len < 0 ? 0 : (kv_len > p.N ? p.N : kv_len);
+    }
 
-    const size_t base = (size_t)bh * p.N * D;
-    const __bf16* __restrict__ Q = p.q + base;
-    const __bf16* __restrict__ K = p.k + base;
-    const __bf16* __restrict__ V = p.v + base;
-    __bf16* __restrict__ O = p.o + base;
+    const int smp = bh / p.H, head = bh % p.H;
+    const Rows Q = rows_of(p.q, smp, head, p.n0), K = rows_of(p.k, smp, head, p.n0);
+    const Rows V = rows_of(p.v, smp, head, p.n0), O = rows_of(p.o, smp, head, p.n0);
 
-    const int T = (kv_len + KT - 1) / KT;         // >= 1
+    const int T = (kv_len + KT - 1) / KT;
+    if (T == 0) {                                 // a sample without valid tokens: its rows are zero
+        f32x16 zero[DB];
+#pragma unroll
+        for (int i = 0; i < DB; ++i)
+#pragma unroll
+            for (int j = 0; j < 16; ++j) zero[i][j] = 0.f;
+        write_output<D>(O, zero, 0.f, q0 + (threadIdx.x >> 6) * 32 + (threadIdx.x & 31), false, p.N, (threadIdx.x & 63) >> 5);
+        return;
+    }
 
 #pragma unroll
     for (int t = 0; t < 3; ++t) {
@@ -832,13 +880,15 @@ __global__ __launch_bounds__(128 * WPG, (D == 64 && WPG == 4 ? 4 : 2)) void attn
     const int wq = wave % WPG;
     const int n = lane & 31;
     const int h = lane >> 5;
-    const int kv_len = p.kv_len;
+    int kv_len = p.kv_len;
+    if (p.kv_lens != nullptr) {                   // per-sample length, clamped to 0..N
+        kv_len = ((const __attribute__((address_space(4))) int32_t*)p.kv_lens)[bh / p.H];
+        kv_len = kv_len < 0 ? 0 : (kv_len > p.N ? p.N : kv_len);
+    }
 
-    const size_t base = (size_t)bh * p.N * D;
-    const __bf16* __restrict__ Q = p.q + base;
-    const __bf16* __restrict__ K = p.k + base;
-    const __bf16* __restrict__ V = p.v + base;
-    __bf16* __restrict__ O = p.o + base;
+    const int smp = bh / p.H, head = bh % p.H;
+    const Rows Q = rows_of(p.q, smp, head, p.n0), K = rows_of(p.k, smp, head, p.n0);
+    const Rows V = rows_of(p.v, smp, head, p.n0), O = rows_of(p.o, smp, head, p.n0);
 
     const int qrow = qi * QT + wq * 32 + n;       // groups share the queries
     const bool qvalid = qrow < kv_len;
@@ -1031,13 +1081,15 @@ __global__ __launch_bounds__(256, (D == 64 ? 4 : 2)) void attn_sparse_sg_kernel(
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int n = lane & 31;
     const int h = lane >> 5;
-    const int kv_len = p.kv_len;
+    int kv_len = p.kv_len;
+    if (p.kv_lens != nullptr) {                   // per-sample length, clamped to 0..N
+        kv_len = ((const __attribute__((address_space(4))) int32_t*)p.kv_lens)[bh / p.H];
+        kv_len = kv_len < 0 ? 0 : (kv_len > p.N ? p.N : kv_len);
+    }
 
-    const size_t base = (size_t)bh * p.N * D;
-    const __bf16* __restrict__ Q = p.q + base;
-    const __bf16* __restrict__ K = p.k + base;
-    const __bf16* __restrict__ V = p.v + base;
-    __bf16* __restrict__ O = p.o + base;
+    const int smp = bh / p.H, head = bh % p.H;
+    const Rows Q = rows_of(p.q, smp, head, p.n0), K = rows_of(p.k, smp, head, p.n0);
+    const Rows V = rows_of(p.v, smp, head, p.n0), O = rows_of(p.o, smp, head, p.n0);
 
     const int qrow = qi * QT + wave * 32 + n;
     const bool qvalid = qrow < kv_len;
@@ -1242,6 +1294,113 @@ int check_common(const void* q, const void* k, const void* v, const void* o,
     return RAPID_OK;
 }
 
+// One validated call: tensors as segment views, sizes, lengths.
+struct Problem {
+    SegTensor q, k, v, o;
+    int n0;
+    int B, H, N, D;
+    int kv_len;
+    const int32_t* kv_lens;
+    float scale;
+};
+
+SegTensor contiguous_bhnd(const void* ptr, int H, int N, int D)
+{
+    SegTensor t;
+    t.seg0 = (const __bf16*)ptr; t.seg1 = nullptr;
+    t.sb0 = (long long)H * N * D; t.sb1 = 0;
+    t.sh = (long long)N * D; t.sn = D;
+    return t;
+}
+
+void fill_common(AttnParams& p, const Problem& pr)
+{
+    p.q = pr.q; p.k = pr.k; p.v = pr.v; p.o = pr.o;
+    p.kv_lens = pr.kv_lens;
+    p.n0 = pr.n0;
+    p.H = pr.H; p.N = pr.N; p.kv_len = pr.kv_len;
+    p.c = pr.scale * LOG2E;
+}
+
+int run_dense(const Problem& pr, void* stream)
+{
+    AttnParams p{};
+    fill_common(p, pr);
+    p.counts = nullptr; p.order = nullptr; p.index = nullptr;
+    p.nq = (pr.N + DENSE_QT - 1) / DENSE_QT;
+    const long long items = (long long)pr.B * pr.H * p.nq;
+    if (items > 0x7fffffffLL / 2) return RAPID_ERR_SHAPE;
+    p.items = (int)items;
+    p.chunk = (p.items + XCDS - 1) / XCDS;
+    p.block = 0; p.nb = 0; p.sub_shift = 0;
+    hipStream_t s = (hipStream_t)stream;
+    const int grid = p.chunk * XCDS;
+    if (pr.D == 64) hipLaunchKernelGGL((attn_dense_pp_kernel<64>), dim3(grid), dim3(512), 0, s, p);
+    else hipLaunchKernelGGL((attn_dense_pp_kernel<128>), dim3(grid), dim3(512), 0, s, p);
+    return hipGetLastError() == hipSuccess ? RAPID_OK : RAPID_ERR_DEVICE;
+}
+
+// nb = ceil(N / block): the last mask block may be ragged (it then ends at N)
+int run_sparse(const Problem& pr, int block, const unsigned char* mask, void* workspace, size_t workspace_bytes,
+               void* stream)
+{
+    const int B = pr.B, H = pr.H, N = pr.N, D = pr.D;
+    const int nb = (N + block - 1) / block;
+    const long long rows = (long long)B * H * nb;
+    if (rows > 0x7fffffffLL / 16) return RAPID_ERR_SHAPE;
+    const WorkspaceLayout w = workspace_layout(B, H, nb, D, block);
+    if (!workspace || workspace_bytes < w.total) return RAPID_ERR_WORKSPACE;
+    if (!aligned16(workspace)) return RAPID_ERR_ALIGN;
+
+    char* ws = (char*)workspace;
+    int32_t* counts = (int32_t*)(ws + w.counts_off);
+    int32_t* order = (int32_t*)(ws + w.order_off);
+    int32_t* index = (int32_t*)(ws + w.index_off);
+    hipStream_t s = (hipStream_t)stream;
+
+    hipLaunchKernelGGL(compact_mask_kernel, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, s,
+                       mask, (int)rows, nb, block, pr.kv_len, pr.kv_lens, H * nb, N, counts, index);
+    if (hipGetLastError() != hipSuccess) return RAPID_ERR_DEVICE;
+    if (block == 128)
+        hipLaunchKernelGGL(plan_split_kernel, dim3(XCDS), dim3(1024), 0, s, counts, B * H, nb, w.chunk,
+                           w.pmax, (PlanRec*)order, (int32_t*)(ws + w.arrived_off));
+    else
+        hipLaunchKernelGGL(plan_kernel, dim3(XCDS), dim3(1024), 0, s, counts, B * H, nb, w.chunk, order);
+    if (hipGetLastError() != hipSuccess) return RAPID_ERR_DEVICE;
+
+    AttnParams p{};
+    fill_common(p, pr);
+    p.counts = counts; p.order = order; p.index = index;
+    p.arrived = (int32_t*)(ws + w.arrived_off);
+    p.partial = ws + w.partial_off;
+    p.nq = nb;
+    p.items = (int)rows;
+    p.chunk = w.chunk;
+    p.block = block; p.nb = nb; p.sub_shift = block == 128 ? 1 : 0;
+    const dim3 grid((unsigned)w.chunk * XCDS);
+    if (block == 128) {
+        if (D == 64) hipLaunchKernelGGL((attn_sparse_sg_kernel<64>), grid, dim3(256), 0, s, p);
+        else hipLaunchKernelGGL((attn_sparse_sg_kernel<128>), grid, dim3(256), 0, s, p);
+    } else {
+        if (D == 64) hipLaunchKernelGGL((attn_sparse_pp_kernel<64, 2>), grid, dim3(256), 0, s, p);
+        else hipLaunchKernelGGL((attn_sparse_pp_kernel<128, 2>), grid, dim3(256), 0, s, p);
+    }
+    return hipGetLastError() == hipSuccess ? RAPID_OK : RAPID_ERR_DEVICE;
+}
+
+Problem contiguous_problem(const void* q, const void* k, const void* v, void* o, int B, int H, int N, int D,
+                           int kv_len, float scale)
+{
+    Problem pr;
+    pr.q = contiguous_bhnd(q, H, N, D); pr.k = contiguous_bhnd(k, H, N, D);
+    pr.v = contiguous_bhnd(v, H, N, D); pr.o = contiguous_bhnd(o, H, N, D);
+    pr.n0 = N;
+    pr.B = B; pr.H = H; pr.N = N; pr.D = D;
+    pr.kv_len = kv_len; pr.kv_lens = nullptr;
+    pr.scale = scale > 0.f ? scale : 1.0f / sqrtf((float)D);
+    return pr;
+}
+
 }  // namespace
 
 extern "C" {
@@ -1253,24 +1412,7 @@ int rapid_attn_dense(const void* q, const void* k, const void* v, void* o,
     (void)workspace; (void)workspace_bytes;
     const int rc = check_common(q, k, v, o, B, H, N, D, kv_len);
     if (rc != RAPID_OK) return rc;
-    if (!(scale > 0.f)) scale = 1.0f / sqrtf((float)D);
-
-    AttnParams p{};
-    p.q = (const __bf16*)q; p.k = (const __bf16*)k; p.v = (const __bf16*)v; p.o = (__bf16*)o;
-    p.counts = nullptr; p.order = nullptr; p.index = nullptr;
-    p.H = H; p.N = N; p.kv_len = kv_len;
-    p.nq = (N + DENSE_QT - 1) / DENSE_QT;
-    const long long items = (long long)B * H * p.nq;
-    if (items > 0x7fffffffLL / 2) return RAPID_ERR_SHAPE;
-    p.items = (int)items;
-    p.chunk = (p.items + XCDS - 1) / XCDS;
-    p.block = 0; p.nb = 0; p.sub_shift = 0;
-    p.c = scale * LOG2E;
-    hipStream_t s = (hipStream_t)stream;
-    const int grid = p.chunk * XCDS;
-    if (D == 64) hipLaunchKernelGGL((attn_dense_pp_kernel<64>), dim3(grid), dim3(512), 0, s, p);
-    else hipLaunchKernelGGL((attn_dense_pp_kernel<128>), dim3(grid), dim3(512), 0, s, p);
-    return hipGetLastError() == hipSuccess ? RAPID_OK : RAPID_ERR_DEVICE;
+    return run_dense(contiguous_problem(q, k, v, o, B, H, N, D, kv_len, scale), stream);
 }
 
 int rapid_attn_block_sparse(const void* q, const void* k, const void* v, void* o,
@@ -1279,54 +1421,82 @@ int rapid_attn_block_sparse(const void* q, const void* k, const void* v, void* o
                             void* workspace, size_t workspace_bytes, void* stream)
 {
     if (!mask) return RAPID_ERR_NULL;
-    int rc = check_common(q, k, v, o, B, H, N, D, kv_len);
+    const int rc = check_common(q, k, v, o, B, H, N, D, kv_len);
     if (rc != RAPID_OK) return rc;
     if (block != 64 && block != 128) return RAPID_ERR_UNSUPPORTED;
     if (N % block != 0) return RAPID_ERR_SHAPE;
-    const int nb = N / block;
-    const long long rows = (long long)B * H * nb;
-    if (rows > 0x7fffffffLL / 16) return RAPID_ERR_SHAPE;
-    const WorkspaceLayout w = workspace_layout(B, H, nb, D, block);
-    if (!workspace || workspace_bytes < w.total) return RAPID_ERR_WORKSPACE;
-    if (!aligned16(workspace)) return RAPID_ERR_ALIGN;
-    if (!(scale > 0.f)) scale = 1.0f / sqrtf((float)D);
+    return run_sparse(contiguous_problem(q, k, v, o, B, H, N, D, kv_len, scale), block, mask, workspace,
+                      workspace_bytes, stream);
+}
 
-    char* ws = (char*)workspace;
-    int32_t* counts = (int32_t*)(ws + w.counts_off);
-    int32_t* order = (int32_t*)(ws + w.order_off);
-    int32_t* index = (int32_t*)(ws + w.index_off);
-    hipStream_t s = (hipStream_t)stream;
-
-    hipLaunchKernelGGL(compact_mask_kernel, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, s,
-                       mask, (int)rows, nb, block, kv_len, counts, index);
-    if (hipGetLastError() != hipSuccess) return RAPID_ERR_DEVICE;
-    if (block == 128)
-        hipLaunchKernelGGL(plan_split_kernel, dim3(XCDS), dim3(1024), 0, s, counts, B * H, nb, w.chunk,
-                           w.pmax, (PlanRec*)order, (int32_t*)(ws + w.arrived_off));
-    else
-        hipLaunchKernelGGL(plan_kernel, dim3(XCDS), dim3(1024), 0, s, counts, B * H, nb, w.chunk, order);
-    if (hipGetLastError() != hipSuccess) return RAPID_ERR_DEVICE;
-
-    AttnParams p{};
-    p.q = (const __bf16*)q; p.k = (const __bf16*)k; p.v = (const __bf16*)v; p.o = (__bf16*)o;
-    p.counts = counts; p.order = order; p.index = index;
-    p.arrived = (int32_t*)(ws + w.arrived_off);
-    p.partial = ws + w.partial_off;
-    p.H = H; p.N = N; p.kv_len = kv_len;
-    p.nq = nb;
-    p.items = (int)rows;
-    p.chunk = w.chunk;
-    p.block = block; p.nb = nb; p.sub_shift = block == 128 ? 1 : 0;
-    p.c = scale * LOG2E;
-    const dim3 grid((unsigned)w.chunk * XCDS);
-    if (block == 128) {
-        if (D == 64) hipLaunchKernelGGL((attn_sparse_sg_kernel<64>), grid, dim3(256), 0, s, p);
-        else hipLaunchKernelGGL((attn_sparse_sg_kernel<128>), grid, dim3(256), 0, s, p);
-    } else {
-        if (D == 64) hipLaunchKernelGGL((attn_sparse_pp_kernel<64, 2>), grid, dim3(256), 0, s, p);
-        else hipLaunchKernelGGL((attn_sparse_pp_kernel<128, 2>), grid, dim3(256), 0, s, p);
+int rapid_attn_joint(const rapid_attn_segment* segments, int n_segments, int B, int H, int D,
+                     int block, const unsigned char* mask, int kv_len, const int* kv_lens, float scale,
+                     void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (!segments) return RAPID_ERR_NULL;
+    if (n_segments != 1 && n_segments != 2) return RAPID_ERR_SHAPE;
+    if (B <= 0 || H <= 0) return RAPID_ERR_SHAPE;
+    if (D != 64 && D != 128) return RAPID_ERR_UNSUPPORTED;
+    if (mask && block != 64 && block != 128) return RAPID_ERR_UNSUPPORTED;
+    long long N = 0;
+    for (int i = 0; i < n_segments; ++i) {
+        const rapid_attn_segment& g = segments[i];
+        if (!g.q || !g.k || !g.v || !g.o) return RAPID_ERR_NULL;
+        if (g.n <= 0) return RAPID_ERR_SHAPE;
+        if (!aligned16(g.q) || !aligned16(g.k) || !aligned16(g.v) || !aligned16(g.o)) return RAPID_ERR_ALIGN;
+        const long long st[6] = {g.in_stride_b, g.in_stride_h, g.in_stride_n, g.out_stride_b, g.out_stride_h, g.out_stride_n};
+        for (int j = 0; j < 6; ++j) {
+            if (st[j] < 0 || st[j] > (1LL << 40)) return RAPID_ERR_SHAPE;
+            if (st[j] % 8 != 0) return RAPID_ERR_ALIGN;            // every row starts on 16 bytes
+        }
+        // rows are D contiguous elements; byte offsets inside a 64-row tile stay below 2^31
+        if (g.in_stride_n < D || g.out_stride_n < D || g.in_stride_n > (1LL << 23) || g.out_stride_n > (1LL << 23)) return RAPID_ERR_SHAPE;
+        N += g.n;
     }
-    return hipGetLastError() == hipSuccess ? RAPID_OK : RAPID_ERR_DEVICE;
+    if (N > (1 << 22)) return RAPID_ERR_SHAPE;
+    if ((long long)B * H > 0x7fffffffLL / 4096) return RAPID_ERR_SHAPE;
+    if (n_segments == 2) {
+        // tiles of 64 keys and mask blocks of 128 queries must not straddle the two tensors
+        if (segments[0].n % 128 != 0) return RAPID_ERR_SHAPE;
+        if (segments[0].in_stride_h != segments[1].in_stride_h || segments[0].in_stride_n != segments[1].in_stride_n ||
+            segments[0].out_stride_h != segments[1].out_stride_h || segments[0].out_stride_n != segments[1].out_stride_n)
+            return RAPID_ERR_SHAPE;
+    }
+    if (kv_len == 0) kv_len = (int)N;
+    if (kv_len < 1 || kv_len > N) return RAPID_ERR_SHAPE;
+
+    Problem pr;
+    auto view = [&](int which) {
+        SegTensor t;
+        const rapid_attn_segment& a = segments[0];
+        const rapid_attn_segment* b2 = n_segments == 2 ? &segments[1] : nullptr;
+        const void* p0 = which == 0 ? a.q : which == 1 ? a.k : which == 2 ? a.v : (const void*)a.o;
+        const void* p1 = !b2 ? nullptr : which == 0 ? b2->q : which == 1 ? b2->k : which == 2 ? b2->v : (const void*)b2->o;
+        t.seg0 = (const __bf16*)p0; t.seg1 = (const __bf16*)p1;
+        const bool out = which == 3;
+        t.sb0 = out ? a.out_stride_b : a.in_stride_b;
+        t.sb1 = !b2 ? 0 : (out ? b2->out_stride_b : b2->in_stride_b);
+        t.sh = out ? a.out_stride_h : a.in_stride_h;
+        t.sn = out ? a.out_stride_n : a.in_stride_n;
+        return t;
+    };
+    pr.q = view(0); pr.k = view(1); pr.v = view(2); pr.o = view(3);
+    pr.n0 = n_segments == 2 ? segments[0].n : (int)N;
+    pr.B = B; pr.H = H; pr.N = (int)N; pr.D = D;
+    pr.kv_len = kv_len; pr.kv_lens = kv_lens;
+    pr.scale = scale > 0.f ? scale : 1.0f / sqrtf((float)D);
+    if (!mask) return run_dense(pr, stream);
+    return run_sparse(pr, block, mask, workspace, workspace_bytes, stream);
+}
+
+size_t rapid_attn_joint_workspace_bytes(int B, int H, int N, int D, int block)
+{
+    if (B <= 0 || H <= 0 || N <= 0 || N > (1 << 22)) return 0;
+    if (D != 64 && D != 128) return 0;
+    if (block != 64 && block != 128) return 0;
+    const int nb = (N + block - 1) / block;
+    if ((long long)B * H * nb > 0x7fffffffLL / 16) return 0;
+    return workspace_layout(B, H, nb, D, block).total;
 }
 
 size_t rapid_attn_workspace_bytes(int B, int H, int N, int D, int block)

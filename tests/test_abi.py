@@ -109,3 +109,43 @@ def test_product_package_does_not_touch_the_oracle():
                 assert "oracle" not in text.lower(), f
     orc = open(os.path.join(ROOT, "oracle", "__init__.py")).read()
     assert "paper_2509_22323_amd" not in orc
+
+
+# ---------------------------------------------------------------- rapid_attn_joint
+def seg(n=256, q=A, k=A + 0x100000, v=A + 0x200000, o=A + 0x300000, H=2, D=64, **over):
+    g = binding.Segment()
+    g.q, g.k, g.v, g.o, g.n = q, k, v, o, n
+    g.in_stride_b, g.in_stride_h, g.in_stride_n = n * H * D, D, H * D
+    g.out_stride_b, g.out_stride_h, g.out_stride_n = n * H * D, D, H * D
+    for name, val in over.items():
+        setattr(g, name, val)
+    return g
+
+
+def joint(segs, B=1, H=2, D=64, block=128, mask=None, kv_len=0, ws=None, ws_bytes=0):
+    arr = (binding.Segment * max(len(segs), 1))(*segs)
+    return ra.library().rapid_attn_joint(arr if segs else None, len(segs), B, H, D, block, mask, kv_len, None, 0.0,
+                                         ws, ws_bytes, None)
+
+
+def test_joint_argument_errors_come_before_any_launch():
+    S = ra.STATUS
+    assert joint([]) == S["RAPID_ERR_NULL"]
+    assert joint([seg(), seg(), seg()]) == S["RAPID_ERR_SHAPE"]
+    assert joint([seg(q=None)]) == S["RAPID_ERR_NULL"]
+    assert joint([seg(n=0)]) == S["RAPID_ERR_SHAPE"]
+    assert joint([seg(q=A + 8)]) == S["RAPID_ERR_ALIGN"]
+    assert joint([seg(in_stride_n=2 * 64 + 4)]) == S["RAPID_ERR_ALIGN"]      # rows off the 16-byte grid
+    assert joint([seg(in_stride_n=32)]) == S["RAPID_ERR_SHAPE"]              # rows overlap
+    assert joint([seg(out_stride_n=1 << 24)]) == S["RAPID_ERR_SHAPE"]
+    assert joint([seg()], D=96) == S["RAPID_ERR_UNSUPPORTED"]
+    assert joint([seg()], block=32, mask=A) == S["RAPID_ERR_UNSUPPORTED"]
+    assert joint([seg()], kv_len=257) == S["RAPID_ERR_SHAPE"]
+    assert joint([seg(n=200), seg(n=77)]) == S["RAPID_ERR_SHAPE"]            # first segment not a multiple of 128
+    assert joint([seg(n=256), seg(n=77, in_stride_n=3 * 2 * 64)]) == S["RAPID_ERR_SHAPE"]   # token strides differ
+    assert joint([seg(n=256), seg(n=77)], mask=A, ws=None) == S["RAPID_ERR_WORKSPACE"]
+    need = ra.rapid_attn_joint_workspace_bytes(1, 2, 333, 64, 128)
+    assert need > 0 and need == ra.rapid_attn_joint_workspace_bytes(1, 2, 384, 64, 128)
+    assert need == ra.rapid_attn_workspace_bytes(1, 2, 384, 64, 128)
+    assert joint([seg(n=256), seg(n=77)], mask=A, ws=WS, ws_bytes=need - 1) == S["RAPID_ERR_WORKSPACE"]
+    assert ra.rapid_attn_joint_workspace_bytes(1, 2, 0, 64, 128) == 0
