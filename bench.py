@@ -62,6 +62,7 @@ def parse():
     ap.add_argument("--no-mfma-probe", action="store_true")
     ap.add_argument("--no-cache-ops", action="store_true")
     ap.add_argument("--no-joint", action="store_true")
+    ap.add_argument("--no-mask-select", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain device copy of the Q tensor (known size) so that HBM "
@@ -210,6 +211,28 @@ def main():
                                "ms": round(j_mean, 5), "tflops": round(dense_flops / (j_mean * 1e-3) / 1e12, 2),
                                "time_over_contiguous": round(j_mean / ev_mean, 3)}
         del segs
+
+    # ---- block-mask selection for the Sparse-Attention levels (block means -> softmax -> mass cut):
+    # streams Q and K once (HBM-bound), then one wavefront per mask row
+    if not args.no_mask_select and w.N % w.block == 0 and w.N // w.block <= 2048:
+        nbk = w.N // w.block
+        sel_mask = torch.empty(w.B, w.H, nbk, nbk, dtype=torch.uint8, device="cuda")
+        sel_ws = torch.empty(ra.rapid_mask_select_workspace_bytes(w.B, w.H, w.N, w.D, w.block), dtype=torch.uint8,
+                             device="cuda")
+        text_start = w.N - 512 if w.N > 1024 else w.N
+        levels = []
+        for action in (1, 2, 3):
+            tau = ra.rapid_mask_level_tau(action)
+            _, m_mean, m_min = time_calls(
+                lambda: ra.rapid_mask_select(dq, dk, sel_mask, w.block, w.kv_len, text_start, tau, 0.0, sel_ws), 100, 10)
+            levels.append({"action": action, "tau": round(tau, 3), "ms": round(m_mean, 5),
+                           "kept_fraction_on_this_input": round(float(sel_mask.float().mean()), 4)})
+        read_bytes = 2 * dq.numel() * 2
+        gbs = read_bytes / (levels[0]["ms"] * 1e-3) / 1e9
+        out["mask_select"] = {"levels": levels,
+                              "roofline": {"bound": "hbm", "kernel": "block_mean_kernel (+ select_blocks_kernel in the time)",
+                                           "achieved": round(gbs, 1), "peak": 8000.0, "unit": "GB/s",
+                                           "frac": round(gbs / 8000.0, 4), "algorithmic_bytes": read_bytes}}
 
     # ---- Cache-Reuse residual operations (O = X + Delta, Delta = G(X) - X): streaming kernels,
     # bound by HBM (6 bytes per element).  Two sizes: the latent of one image at this workload's

@@ -1,0 +1,78 @@
+/*
+ * rapid_mask.h -- C ABI of the block-mask selection that turns a Sparse-Attention
+ * level into the mask rapid_attn_block_sparse takes; exported by the same shared
+ * library as rapid_attn.h.
+ *
+ * RAPID^3 (Sec. 3.2 "Level-3: Sparse-Attention", Sec. 3.3 (c)) lets the policy pick,
+ * per step, one of N_sparse = 3 candidate settings of increasing sparsity for a
+ * sparse attention that prunes the attention map per layer and head; the paper
+ * takes that sparse attention from prior work and does not state its pruning
+ * rule.  The rule here is this library's own, of the kind the paper describes
+ * (a cheap per-head prediction of which blocks of the map matter):
+ *
+ *   for every (sample, head), with nb = N/block mask blocks, live blocks = those
+ *   that start below kv_len:
+ *   1. qbar_i, kbar_j = means of Q, K over the valid tokens of block i, j
+ *   2. phat_i = softmax over the live j of scale * qbar_i . kbar_j
+ *   3. row i keeps the fewest key-blocks, taken by decreasing phat_ij, whose mass
+ *      reaches tau (blocks tying with the last one taken are kept as well);
+ *      tau >= 1 keeps every live block
+ *   4. always kept: the diagonal, and the rows and columns of text blocks (blocks
+ *      holding a token at or after text_start) -- the paper's settings keep the
+ *      text tokens dense
+ *   5. rows and columns of blocks that are not live are 0
+ *
+ * Arithmetic: bf16 inputs, fp32 sums and softmax; the cut compares fp32 partial
+ * sums, so a block whose inclusion decides whether the mass reaches tau to within
+ * rounding may fall on either side.
+ *
+ * Memory: q, k, mask, workspace are DEVICE pointers owned by the caller; q, k are
+ * bf16 [B,H,N,D] contiguous and read-only; mask is fully overwritten.  Nothing is
+ * allocated, no state is kept, nothing synchronises; kernels go to `stream`.
+ * Errors are found on the host before any launch (status codes of rapid_attn.h):
+ * RAPID_ERR_NULL, RAPID_ERR_SHAPE (B,H,N <= 0, kv_len outside 1..N, N % block != 0,
+ * text_start < 0, tau <= 0 or NaN), RAPID_ERR_UNSUPPORTED (D not 64/128, block not
+ * 64/128, more than 2048 mask blocks), RAPID_ERR_ALIGN, RAPID_ERR_WORKSPACE,
+ * RAPID_ERR_DEVICE.
+ */
+#ifndef RAPID_MASK_H
+#define RAPID_MASK_H
+
+#include <stddef.h>
+#include "rapid_attn.h"
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/*
+ *   q, k        device, bf16 [B,H,N,D]
+ *   block       mask tile edge, 64 or 128; N % block == 0; N/block <= 2048
+ *   kv_len      valid tokens, 1..N
+ *   text_start  first text token (tokens are image first, then text); a value
+ *               >= kv_len means there are no text blocks
+ *   tau         mass each row keeps, > 0; >= 1 keeps every live block
+ *   scale       score scale; <= 0 selects 1/sqrt(D)
+ *   mask        device, uint8 [B,H,N/block,N/block], written with 0/1
+ *   workspace   device, at least rapid_mask_select_workspace_bytes(...) bytes,
+ *               16-byte aligned: the fp32 block means of Q and K
+ */
+RAPID_API int rapid_mask_select(const void* q, const void* k, int B, int H, int N, int D,
+                                int block, int kv_len, int text_start, float tau, float scale,
+                                unsigned char* mask, void* workspace, size_t workspace_bytes,
+                                void* stream);
+
+/* Workspace bytes of rapid_mask_select; 0 if the shape is invalid or unsupported. */
+RAPID_API size_t rapid_mask_select_workspace_bytes(int B, int H, int N, int D, int block);
+
+/*
+ * The library's default tau for a Sparse-Attention action (Sec. 3.3 (c)): action 0
+ * (full attention) -> 1.0, actions 1, 2, 3 -> 0.98, 0.95, 0.90 (progressively
+ * sparser; values of this library, not of the paper); anything else -> NaN.
+ */
+RAPID_API float rapid_mask_level_tau(int action);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* RAPID_MASK_H */

@@ -30,6 +30,7 @@ class Segment(ctypes.Structure):
                 ("in_stride_b", ctypes.c_longlong), ("in_stride_h", ctypes.c_longlong), ("in_stride_n", ctypes.c_longlong),
                 ("out_stride_b", ctypes.c_longlong), ("out_stride_h", ctypes.c_longlong),
                 ("out_stride_n", ctypes.c_longlong)]
+MASK_EXPORTS = ("rapid_mask_select", "rapid_mask_select_workspace_bytes", "rapid_mask_level_tau")
 CACHE_EXPORTS = ("rapid_cache_store", "rapid_cache_reuse", "rapid_equivalent_steps", "rapid_reward")
 
 
@@ -79,6 +80,12 @@ def library():
     lib.rapid_attn_status_string.restype = ctypes.c_char_p
     lib.rapid_attn_version.argtypes = []
     lib.rapid_attn_version.restype = ci
+    lib.rapid_mask_select.argtypes = [vp, vp, ci, ci, ci, ci, ci, ci, ci, cf, cf, vp, vp, sz, vp]
+    lib.rapid_mask_select.restype = ci
+    lib.rapid_mask_select_workspace_bytes.argtypes = [ci, ci, ci, ci, ci]
+    lib.rapid_mask_select_workspace_bytes.restype = sz
+    lib.rapid_mask_level_tau.argtypes = [ci]
+    lib.rapid_mask_level_tau.restype = cf
     cd, dp = ctypes.c_double, ctypes.POINTER(ctypes.c_double)
     lib.rapid_cache_store.argtypes = [vp, vp, vp, ci, sz, vp, vp]
     lib.rapid_cache_store.restype = ci
@@ -268,3 +275,38 @@ def rapid_equivalent_steps(c_cache, c_sparse):
 
 def rapid_reward(q, d, K, lam=0.97, omega=1.0):
     return library().rapid_reward(float(q), float(d), float(omega), float(lam), int(K))
+
+
+# ---------------------------------------------------------------- block-mask selection
+def rapid_mask_level_tau(action: int) -> float:
+    return float(library().rapid_mask_level_tau(int(action)))
+
+
+def rapid_mask_select_workspace_bytes(B: int, H: int, N: int, D: int, block: int) -> int:
+    return int(library().rapid_mask_select_workspace_bytes(B, H, N, D, block))
+
+
+def rapid_mask_select(q, k, mask, block, kv_len=None, text_start=None, tau=0.95, scale=0.0, workspace=None):
+    """mask <- block mask [B,H,N/block,N/block] (uint8) keeping, per row, the key-blocks that hold
+    `tau` of the pooled attention mass, plus the diagonal and the text rows/columns.  q, k: CUDA
+    bf16 [B,H,N,D] contiguous."""
+    import torch
+    for name, t in (("q", q), ("k", k)):
+        if not (isinstance(t, torch.Tensor) and t.is_cuda and t.dtype == torch.bfloat16 and t.dim() == 4
+                and t.is_contiguous() and t.shape == q.shape and t.device == q.device):
+            raise TypeError(f"{name} must be a contiguous CUDA bfloat16 tensor [B,H,N,D]")
+    B, H, N, D = (int(x) for x in q.shape)
+    kv_len = N if kv_len is None else int(kv_len)
+    text_start = N if text_start is None else int(text_start)
+    if not (isinstance(mask, torch.Tensor) and mask.is_cuda and mask.dtype == torch.uint8 and mask.is_contiguous()
+            and mask.device == q.device):
+        raise TypeError("mask must be a contiguous CUDA uint8 tensor")
+    if block > 0 and N % block == 0 and tuple(mask.shape) != (B, H, N // block, N // block):
+        raise ValueError(f"mask shape {tuple(mask.shape)} != {(B, H, N // block, N // block)}")
+    if workspace is None:
+        workspace = torch.empty(max(rapid_mask_select_workspace_bytes(B, H, N, D, int(block)), 16), dtype=torch.uint8,
+                                device=q.device)
+    _check(library().rapid_mask_select(q.data_ptr(), k.data_ptr(), B, H, N, D, int(block), kv_len, text_start,
+                                       float(tau), float(scale), mask.data_ptr(), workspace.data_ptr(),
+                                       workspace.numel() * workspace.element_size(), _stream(q)))
+    return mask

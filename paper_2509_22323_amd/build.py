@@ -7,7 +7,8 @@ import sys
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
-SOURCES = [os.path.join(HERE, "csrc", "rapid_attn.hip"), os.path.join(HERE, "csrc", "rapid_cache.hip")]
+SOURCES = [os.path.join(HERE, "csrc", "rapid_attn.hip"), os.path.join(HERE, "csrc", "rapid_cache.hip"),
+           os.path.join(HERE, "csrc", "rapid_mask.hip")]
 OUT = os.path.join(HERE, "librapid_attn.so")
 # measurement aid used by bench.py only (an MFMA-only loop), kept out of the attention library
 PROBE_SOURCES = [os.path.join(HERE, "csrc", "mfma_probe.hip")]

@@ -1,0 +1,230 @@
+// Block-mask selection for the Sparse-Attention levels, MI355X (gfx950).  C ABI and the rule:
+// include/rapid_mask.h (RAPID^3 Sec. 3.2 Level-3 and Sec. 3.3 (c) describe what the mask is
+// for; the rule is this library's own).
+//
+// Two kernels.  block_mean_kernel streams Q and K once (HBM-bound: 2 bytes per element read,
+// 4 * D bytes per block written) and leaves fp32 block means in the workspace.
+// select_blocks_kernel gives every mask row to one wavefront: scores against all key-block
+// means, softmax, and the cumulative-mass cut found without sorting, by bisection over the
+// bit patterns of the (positive) probabilities.
+#include <hip/hip_runtime.h>
+#include <math.h>
+#include <stdint.h>
+
+#include "rapid_mask.h"
+
+namespace {
+
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int MAX_NB = 2048;      // mask blocks per side the selection kernel holds in LDS
+
+// means[(which, bh, i), :] = mean over the valid rows of block i of Q (which = 0) or K (1).
+// 256 threads: D/8 column groups of 8 elements x 256/(D/8) row groups; every thread adds up
+// its rows in increasing order, the row groups are then added in increasing order.
+template <int D>
+__global__ __launch_bounds__(256) void block_mean_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
+                                                         int N, int block, int kv_len, int nb, float* __restrict__ means,
+                                                         size_t which_stride)
+{
+    constexpr int CG = D / 8, RG = 256 / CG;
+    __shared__ float red[RG][D];
+    const int i = blockIdx.x % nb, bh = blockIdx.x / nb, which = blockIdx.y;
+    const uint16_t* src = (which ? k : q) + (size_t)bh * N * D;
+    const int lo = i * block;
+    int hi = lo + block;
+    hi = hi < kv_len ? hi : kv_len;
+    const int c = threadIdx.x % CG, g = threadIdx.x / CG;
+    float acc[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc[e] = 0.f;
+    for (int r = lo + g; r < hi; r += RG) {
+        const u32x4 v = *(const u32x4*)(src + (size_t)r * D + c * 8);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            acc[2 * e] += __uint_as_float(v[e] << 16);
+            acc[2 * e + 1] += __uint_as_float(v[e] & 0xffff0000u);
+        }
+    }
+#pragma unroll
+    for (int e = 0; e < 8; ++e) red[g][c * 8 + e] = acc[e];
+    __syncthreads();
+    if (threadIdx.x < D) {
+        float s = 0.f;
+        for (int gg = 0; gg < RG; ++gg) s += red[gg][threadIdx.x];
+        const int cnt = hi - lo;
+        means[which * which_stride + ((size_t)bh * nb + i) * D + threadIdx.x] = cnt > 0 ? s / (float)cnt : 0.f;
+    }
+}
+
+__device__ __forceinline__ float wave_max(float v)
+{
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) v = fmaxf(v, __shfl_xor(v, d, 64));
+    return v;
+}
+__device__ __forceinline__ float wave_sum(float v)
+{
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) v += __shfl_xor(v, d, 64);
+    return v;
+}
+
+// One wavefront per mask row (b, h, i); four rows per workgroup.
+template <int D>
+__global__ __launch_bounds__(256) void select_blocks_kernel(const float* __restrict__ qmean, const float* __restrict__ kmean,
+                                                            int rows, int nb, int live, int first_text, float tau,
+                                                            float scale, unsigned char* __restrict__ mask)
+{
+    __shared__ float qrow[4][D];
+    __shared__ float prob[4][MAX_NB];
+    const int wv = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int row = blockIdx.x * 4 + wv;
+    if (row >= rows) return;
+    const int i = row % nb;
+    const size_t bh = row / nb;
+    unsigned char* out = mask + (size_t)row * nb;
+    if (i >= live) {
+        for (int j = lane; j < nb; j += 64) out[j] = 0;
+        return;
+    }
+    for (int d = lane; d < D; d += 64) qrow[wv][d] = qmean[(size_t)row * D + d];
+    __builtin_amdgcn_wave_barrier();               // one wavefront: its LDS accesses execute in order
+
+    // scores of the live key-blocks (lane j, j + 64, ...), their maximum
+    const float* kb = kmean + bh * nb * D;
+    float mx = -INFINITY;
+    for (int j = lane; j < live; j += 64) {
+        const f32x4* kr = (const f32x4*)(kb + (size_t)j * D);
+        float dot = 0.f;
+#pragma unroll 4
+        for (int d4 = 0; d4 < D / 4; ++d4) {
+            const f32x4 kv = kr[d4];
+            dot += qrow[wv][4 * d4] * kv[0];
+            dot += qrow[wv][4 * d4 + 1] * kv[1];
+            dot += qrow[wv][4 * d4 + 2] * kv[2];
+            dot += qrow[wv][4 * d4 + 3] * kv[3];
+        }
+        const float s = scale * dot;
+        prob[wv][j] = s;
+        mx = fmaxf(mx, s);
+    }
+    mx = wave_max(mx);
+    // unnormalised probabilities e = exp(s - max) <= 1 and their sum (normalising both sides
+    // of "mass >= tau * total" changes nothing)
+    float part = 0.f;
+    for (int j = lane; j < live; j += 64) {
+        const float e = expf(prob[wv][j] - mx);
+        prob[wv][j] = e;
+        part += e;
+    }
+    const float total = wave_sum(part);
+    // v* = largest probability whose upper set {e >= v*} holds at least tau * total: positive
+    // floats order like their bit patterns, and the mass of the upper set falls as the cut
+    // rises, so bisect over the patterns between 0 and 1.0f.
+    unsigned cut = 0u;
+    if (tau < 1.0f) {
+        const float target = tau * total;
+        unsigned lo = 0u, hi = 0x3F800001u;                  // mass(lo) >= target > mass(hi) = 0
+        while (hi - lo > 1u) {
+            const unsigned mid = lo + (hi - lo) / 2u;
+            float m = 0.f;
+            for (int j = lane; j < live; j += 64) {
+                const float e = prob[wv][j];
+                m += (__float_as_uint(e) >= mid) ? e : 0.f;
+            }
+            m = wave_sum(m);
+            if (m >= target) lo = mid; else hi = mid;
+        }
+        cut = lo;
+    }
+    const bool text_row = i >= first_text;
+    for (int j = lane; j < nb; j += 64) {
+        bool keep = false;
+        if (j < live) keep = text_row || j >= first_text || j == i || __float_as_uint(prob[wv][j]) >= cut;
+        out[j] = keep ? 1 : 0;
+    }
+}
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+size_t means_bytes(int B, int H, int nb, int D) { return (size_t)2 * B * H * nb * D * sizeof(float); }
+
+bool shape_ok(int B, int H, int N, int D, int block)
+{
+    if (B <= 0 || H <= 0 || N <= 0 || N > (1 << 22)) return false;
+    if ((long long)B * H > 0x7fffffffLL / 4096) return false;
+    if (D != 64 && D != 128) return false;
+    if (block != 64 && block != 128) return false;
+    if (N % block != 0 || N / block > MAX_NB) return false;
+    return true;
+}
+
+}  // namespace
+
+extern "C" {
+
+int rapid_mask_select(const void* q, const void* k, int B, int H, int N, int D, int block, int kv_len,
+                      int text_start, float tau, float scale, unsigned char* mask, void* workspace,
+                      size_t workspace_bytes, void* stream)
+{
+    if (!q || !k || !mask) return RAPID_ERR_NULL;
+    if (B <= 0 || H <= 0 || N <= 0 || N > (1 << 22)) return RAPID_ERR_SHAPE;
+    if ((long long)B * H > 0x7fffffffLL / 4096) return RAPID_ERR_SHAPE;
+    if (kv_len < 1 || kv_len > N || text_start < 0 || !(tau > 0.f)) return RAPID_ERR_SHAPE;
+    if (D != 64 && D != 128) return RAPID_ERR_UNSUPPORTED;
+    if (block != 64 && block != 128) return RAPID_ERR_UNSUPPORTED;
+    if (N % block != 0) return RAPID_ERR_SHAPE;
+    const int nb = N / block;
+    if (nb > MAX_NB) return RAPID_ERR_UNSUPPORTED;
+    if (!aligned16(q) || !aligned16(k)) return RAPID_ERR_ALIGN;
+    const size_t need = means_bytes(B, H, nb, D);
+    if (!workspace || workspace_bytes < need) return RAPID_ERR_WORKSPACE;
+    if (!aligned16(workspace)) return RAPID_ERR_ALIGN;
+    if (!(scale > 0.f)) scale = 1.0f / sqrtf((float)D);
+
+    float* means = (float*)workspace;
+    const size_t which_stride = (size_t)B * H * nb * D;
+    hipStream_t s = (hipStream_t)stream;
+    if ((long long)B * H * nb > 0x7fffffffLL / 16) return RAPID_ERR_SHAPE;
+    const dim3 g1((unsigned)(nb * B * H), 2u);
+    if (D == 64)
+        hipLaunchKernelGGL((block_mean_kernel<64>), g1, dim3(256), 0, s, (const uint16_t*)q, (const uint16_t*)k, N, block,
+                           kv_len, nb, means, which_stride);
+    else
+        hipLaunchKernelGGL((block_mean_kernel<128>), g1, dim3(256), 0, s, (const uint16_t*)q, (const uint16_t*)k, N, block,
+                           kv_len, nb, means, which_stride);
+    if (hipGetLastError() != hipSuccess) return RAPID_ERR_DEVICE;
+
+    const int rows = B * H * nb;
+    const int live = (kv_len + block - 1) / block;
+    const int first_text = text_start < kv_len ? text_start / block : nb;
+    const dim3 g2((unsigned)((rows + 3) / 4));
+    if (D == 64)
+        hipLaunchKernelGGL((select_blocks_kernel<64>), g2, dim3(256), 0, s, means, means + which_stride, rows, nb, live,
+                           first_text, tau, scale, mask);
+    else
+        hipLaunchKernelGGL((select_blocks_kernel<128>), g2, dim3(256), 0, s, means, means + which_stride, rows, nb, live,
+                           first_text, tau, scale, mask);
+    return hipGetLastError() == hipSuccess ? RAPID_OK : RAPID_ERR_DEVICE;
+}
+
+size_t rapid_mask_select_workspace_bytes(int B, int H, int N, int D, int block)
+{
+    if (!shape_ok(B, H, N, D, block)) return 0;
+    return means_bytes(B, H, N / block, D);
+}
+
+float rapid_mask_level_tau(int action)
+{
+    switch (action) {
+        case 0: return 1.0f;
+        case 1: return 0.98f;
+        case 2: return 0.95f;
+        case 3: return 0.90f;
+        default: return NAN;
+    }
+}
+
+}  // extern "C"

@@ -1,0 +1,49 @@
+"""Host-only checks of the mask-selection part of the C ABI."""
+import ctypes
+import math
+import os
+import re
+
+import paper_2509_22323_amd as ra
+from oracle import mask_oracle as mo
+from paper_2509_22323_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = open(os.path.join(ROOT, "include", "rapid_mask.h")).read()
+A, M, WS = 0x10000, 0x500000, 0x7000000       # fake aligned "device" addresses: never dereferenced
+
+
+def call(q=A, k=A + 0x100000, B=1, H=2, N=256, D=64, block=64, kv_len=256, text_start=256, tau=0.9, scale=0.0,
+         mask=M, ws=WS, ws_bytes=1 << 30):
+    return ra.library().rapid_mask_select(q, k, B, H, N, D, block, kv_len, text_start, tau, scale, mask, ws, ws_bytes, None)
+
+
+def test_header_and_library_agree():
+    declared = re.findall(r"RAPID_API\s+[\w\s\*]+?\b(rapid_\w+)\s*\(", HEADER)
+    assert set(declared) == set(binding.MASK_EXPORTS)
+    ra.library()
+    lib = ctypes.CDLL(ra.library_path())
+    for name in declared:
+        assert hasattr(lib, name), name
+
+
+def test_argument_errors_come_before_any_launch():
+    S = ra.STATUS
+    assert call(q=None) == S["RAPID_ERR_NULL"] and call(k=None) == S["RAPID_ERR_NULL"] and call(mask=None) == S["RAPID_ERR_NULL"]
+    for bad in (dict(B=0), dict(H=0), dict(N=0), dict(kv_len=0), dict(kv_len=257), dict(text_start=-1),
+                dict(tau=0.0), dict(tau=-1.0), dict(tau=float("nan")), dict(N=320, kv_len=300, block=128)):
+        assert call(**bad) == S["RAPID_ERR_SHAPE"], bad
+    for bad in (dict(D=96), dict(block=32), dict(N=64 * 2049, kv_len=64, block=64)):
+        assert call(**bad) == S["RAPID_ERR_UNSUPPORTED"], bad
+    assert call(q=A + 2) == S["RAPID_ERR_ALIGN"] and call(ws=WS + 4) == S["RAPID_ERR_ALIGN"]
+    need = ra.rapid_mask_select_workspace_bytes(1, 2, 256, 64, 64)
+    assert need == 2 * 1 * 2 * 4 * 64 * 4
+    assert call(ws=None) == S["RAPID_ERR_WORKSPACE"] and call(ws_bytes=need - 1) == S["RAPID_ERR_WORKSPACE"]
+    assert ra.rapid_mask_select_workspace_bytes(1, 2, 250, 64, 64) == 0
+
+
+def test_default_levels_are_nested_and_match_the_oracle_table():
+    taus = [ra.rapid_mask_level_tau(a) for a in range(4)]
+    assert taus[0] == 1.0 and taus == sorted(taus, reverse=True) and len(set(taus)) == 4
+    assert all(abs(t - w) < 1e-7 for t, w in zip(taus, mo.LEVEL_TAU))
+    assert math.isnan(ra.rapid_mask_level_tau(4)) and math.isnan(ra.rapid_mask_level_tau(-1))
