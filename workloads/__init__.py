@@ -217,3 +217,22 @@ def sample_rows(B, H, N, kv_len, block, n, seed):
         seen.add((int(rng.integers(B)), int(rng.integers(H)), int(rng.integers(kv_len))))
     rows = fixed + sorted(seen - set(fixed))
     return np.asarray(rows, dtype=np.int32)
+
+
+def action_trace(seed, n_steps=None, n_cached=None, n_sparse=None):
+    """A scripted action trace of one image with the statistics the paper reports for its learned
+    policies (App. "distribution of learned strategies": 12-16 sampling steps per image, of which
+    4-8 reuse the cache and 2-4 run sparse attention): a list of (a_cache, a_sparse) per step,
+    a_cache in {0, 1}, a_sparse in 0..3 (0 on the steps that reuse the cache, where the sparse
+    policy is inactive).  The first step always computes (there is no cache yet).  Only the
+    counts follow the paper; which steps get which action is a seeded draw."""
+    rng = np.random.default_rng(seed)
+    n_steps = int(rng.integers(12, 17)) if n_steps is None else n_steps
+    n_cached = int(rng.integers(4, 9)) if n_cached is None else n_cached
+    n_sparse = int(rng.integers(2, 5)) if n_sparse is None else n_sparse
+    n_cached = min(n_cached, n_steps - 1)
+    n_sparse = min(n_sparse, n_steps - n_cached)
+    cached = set((1 + rng.choice(n_steps - 1, size=n_cached, replace=False)).tolist())
+    free = [s for s in range(n_steps) if s not in cached]
+    sparse = set(rng.choice(free, size=n_sparse, replace=False).tolist())
+    return [(1, 0) if s in cached else (0, int(rng.integers(1, 4)) if s in sparse else 0) for s in range(n_steps)]
