@@ -147,6 +147,115 @@ __global__ __launch_bounds__(256) void select_blocks_kernel(const float* __restr
     }
 }
 
+// The same for up to SMALL_NB mask blocks per side (every shape of the paper's models): one
+// workgroup per 16 rows of one (sample, head).  The key-block means of the head pass through
+// LDS in chunks of 64 (coalesced loads, rows padded by four floats so that the 16-byte reads
+// of consecutive lanes fall on different banks) and serve all 16 rows; a wavefront owns four
+// rows.  The cut needs neither a sort nor a search here: block j is kept iff the blocks with
+// a strictly larger probability hold less than tau of the mass, a sum each lane forms for its
+// own blocks over all the others (nb^2 work per row, trivial at this size).
+constexpr int SMALL_NB = 256;
+constexpr int SMALL_ROWS = 16;
+
+template <int D>
+__global__ __launch_bounds__(256) void select_blocks_small_kernel(const float* __restrict__ qmean,
+                                                                  const float* __restrict__ kmean, int nb, int live,
+                                                                  int first_text, float tau, float scale,
+                                                                  unsigned char* __restrict__ mask)
+{
+    constexpr int KROW = D + 4;
+    __shared__ __attribute__((aligned(16))) float kch[64 * KROW];
+    __shared__ __attribute__((aligned(16))) float qs[SMALL_ROWS][D];
+    __shared__ float ps[SMALL_ROWS][SMALL_NB];
+    const int groups = (nb + SMALL_ROWS - 1) / SMALL_ROWS;
+    const size_t bh = blockIdx.x / groups;
+    const int i0 = (blockIdx.x % groups) * SMALL_ROWS;
+    const int tid = threadIdx.x, wv = tid >> 6, lane = tid & 63;
+
+    constexpr int KPT = 64 * (D / 4) / 256;                    // 16-byte pieces of a chunk per thread
+    const float* kb = kmean + bh * nb * D;
+    f32x4 kreg[KPT];
+    auto fetch_chunk = [&](int j0) {                           // requested early, stored to LDS later
+#pragma unroll
+        for (int u = 0; u < KPT; ++u) {
+            const int e = tid + u * 256, jr = e / (D / 4), d4 = e % (D / 4);
+            const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+            kreg[u] = (j0 + jr < live) ? *(const f32x4*)(kb + (size_t)(j0 + jr) * D + 4 * d4) : zero;
+        }
+    };
+    fetch_chunk(0);
+    for (int e = tid; e < SMALL_ROWS * D; e += 256) {
+        const int r = e / D, d = e % D;
+        qs[r][d] = (i0 + r < live) ? qmean[(bh * nb + i0 + r) * D + d] : 0.f;
+    }
+    for (int j0 = 0; j0 < live; j0 += 64) {
+        __syncthreads();                                       // previous chunk consumed (and qs written)
+#pragma unroll
+        for (int u = 0; u < KPT; ++u) {
+            const int e = tid + u * 256, jr = e / (D / 4), d4 = e % (D / 4);
+            *(f32x4*)(kch + jr * KROW + 4 * d4) = kreg[u];
+        }
+        if (j0 + 64 < live) fetch_chunk(j0 + 64);              // the next chunk travels during this one's work
+        __syncthreads();
+        float dot[4] = {0.f, 0.f, 0.f, 0.f};
+        const float* kr = kch + lane * KROW;
+#pragma unroll 4
+        for (int d4 = 0; d4 < D / 4; ++d4) {
+            const f32x4 kv = *(const f32x4*)(kr + 4 * d4);
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const f32x4 qv = *(const f32x4*)(&qs[wv * 4 + r][4 * d4]);
+                dot[r] += qv[0] * kv[0];
+                dot[r] += qv[1] * kv[1];
+                dot[r] += qv[2] * kv[2];
+                dot[r] += qv[3] * kv[3];
+            }
+        }
+        if (j0 + lane < live) {
+#pragma unroll
+            for (int r = 0; r < 4; ++r) ps[wv * 4 + r][j0 + lane] = scale * dot[r];
+        }
+    }
+    __builtin_amdgcn_wave_barrier();                           // a wavefront reads only the rows it wrote
+
+    for (int r = 0; r < 4; ++r) {
+        const int row = wv * 4 + r, i = i0 + row;
+        if (i >= nb) break;
+        unsigned char* out = mask + (bh * nb + i) * (size_t)nb;
+        if (i >= live) {
+            for (int j = lane; j < nb; j += 64) out[j] = 0;
+            continue;
+        }
+        float mx = -INFINITY;
+        for (int j = lane; j < live; j += 64) mx = fmaxf(mx, ps[row][j]);
+        mx = wave_max(mx);
+        float part = 0.f;
+        for (int j = lane; j < live; j += 64) {
+            const float e = expf(ps[row][j] - mx);
+            ps[row][j] = e;
+            part += e;
+        }
+        const float target = tau * wave_sum(part);
+        const bool text_row = i >= first_text;
+        for (int j = lane; j < nb; j += 64) {
+            bool keep = false;
+            if (j < live) {
+                keep = text_row || j >= first_text || j == i || tau >= 1.0f;
+                if (!keep) {
+                    const float mine = ps[row][j];
+                    float above = 0.f;                         // mass of the blocks that come before j
+                    for (int k2 = 0; k2 < live; ++k2) {
+                        const float e = ps[row][k2];
+                        above += (e > mine) ? e : 0.f;
+                    }
+                    keep = above < target;
+                }
+            }
+            out[j] = keep ? 1 : 0;
+        }
+    }
+}
+
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 size_t means_bytes(int B, int H, int nb, int D) { return (size_t)2 * B * H * nb * D * sizeof(float); }
@@ -200,6 +309,16 @@ int rapid_mask_select(const void* q, const void* k, int B, int H, int N, int D, 
     const int rows = B * H * nb;
     const int live = (kv_len + block - 1) / block;
     const int first_text = text_start < kv_len ? text_start / block : nb;
+    if (nb <= SMALL_NB) {
+        const dim3 gs((unsigned)(B * H * ((nb + SMALL_ROWS - 1) / SMALL_ROWS)));
+        if (D == 64)
+            hipLaunchKernelGGL((select_blocks_small_kernel<64>), gs, dim3(256), 0, s, means, means + which_stride, nb, live,
+                               first_text, tau, scale, mask);
+        else
+            hipLaunchKernelGGL((select_blocks_small_kernel<128>), gs, dim3(256), 0, s, means, means + which_stride, nb, live,
+                               first_text, tau, scale, mask);
+        return hipGetLastError() == hipSuccess ? RAPID_OK : RAPID_ERR_DEVICE;
+    }
     const dim3 g2((unsigned)((rows + 3) / 4));
     if (D == 64)
         hipLaunchKernelGGL((select_blocks_kernel<64>), g2, dim3(256), 0, s, means, means + which_stride, rows, nb, live,

@@ -57,6 +57,13 @@ def test_mask_matches_the_oracle(B, H, N, D, block, kv_len, text_start, gain, ta
         assert got[:, :, :live, :live].mean() < 0.95           # it does prune on these inputs
 
 
+def test_more_than_256_blocks_per_row_take_the_bisection_kernel():
+    B, H, N, D, block, kv_len = 1, 1, 64 * 300, 64, 64, 64 * 300 - 17
+    q, k, _ = wl.make_qkv(B, H, N, D, kv_len, seed=19, gain=3.0)
+    got = check(q, k, block, kv_len, 64 * 290, 0.7)
+    assert got[0, 0, :290, :290].mean() < 0.9
+
+
 def test_levels_are_nested_and_tau_one_is_dense():
     B, H, N, D, block = 1, 2, 2048, 128, 128
     q, k, _ = wl.make_qkv(B, H, N, D, N, seed=3, gain=3.0)
