@@ -22,7 +22,8 @@
  * Pruned keys are removed before the softmax; K/V tiles of pruned blocks and
  * rows at or beyond kv_len are never multiplied in (NaN/Inf there are inert).
  * Arithmetic: bf16 inputs, bf16 MFMA with fp32 accumulation, fp32 online
- * softmax, probabilities rounded to bf16 before the PV product, bf16 output.
+ * softmax, probabilities rounded to bf16 before the PV product and the
+ * normaliser taken as the fp32 sum of those rounded probabilities, bf16 output.
  *
  * Memory: every pointer except `stream` is a DEVICE pointer owned by the
  * caller.  Q, K, V, O are bf16 [B, H, N, D] contiguous, D fastest.  Q/K/V/mask

@@ -581,41 +581,27 @@ __device__ __forceinline__ void softmax_tile(const f32x16 (&st)[2], f32x16 (&acc
     }
     const float mc = st_.m * c;
     float rs0 = 0.f, rs1 = 0.f;
-    if constexpr (D == 64) {
-        // At D = 64 the softmax phase is the longer one: add the row sum up two probabilities
-        // per instruction (v_dot2 of the bf16 pair against 1.0).  The sum is then over the
-        // probabilities as rounded to bf16, the weights the PV product really applies.  (At
-        // D = 128 the same change costs 4 %: the dot product competes with the MFMAs.)
-        typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
-        bf16x2 ones;
-        ones[0] = (__bf16)1.0f;
-        ones[1] = (__bf16)1.0f;
+    // The row sum adds up the probabilities two per instruction (v_dot2 of the bf16 pair
+    // against 1.0): the softmax phase is the one the slots wait for.  The sum is then over the
+    // probabilities as rounded to bf16, the weights the PV product really applies.
+    typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+    bf16x2 ones;
+    ones[0] = (__bf16)1.0f;
+    ones[1] = (__bf16)1.0f;
 #pragma unroll
-        for (int g = 0; g < 4; ++g) {
-            const int rb = g >> 1, t = g & 1;
+    for (int g = 0; g < 4; ++g) {
+        const int rb = g >> 1, t = g & 1;
 #pragma unroll
-            for (int i = 0; i < 8; i += 2) {
-                const float e0 = __builtin_amdgcn_exp2f(__builtin_fmaf(st[rb][8 * t + i], c, -mc));
-                const float e1 = __builtin_amdgcn_exp2f(__builtin_fmaf(st[rb][8 * t + i + 1], c, -mc));
-                bf16x2 pr;
-                pr[0] = (__bf16)e0;
-                pr[1] = (__bf16)e1;
-                pb[g][i] = pr[0];
-                pb[g][i + 1] = pr[1];
-                if (i & 2) rs1 = __builtin_amdgcn_fdot2_f32_bf16(pr, ones, rs1, false);
-                else rs0 = __builtin_amdgcn_fdot2_f32_bf16(pr, ones, rs0, false);
-            }
-        }
-    } else {
-#pragma unroll
-        for (int g = 0; g < 4; ++g) {
-            const int rb = g >> 1, t = g & 1;
-#pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                const float e = __builtin_amdgcn_exp2f(__builtin_fmaf(st[rb][8 * t + i], c, -mc));
-                if (i & 1) rs1 += e; else rs0 += e;
-                pb[g][i] = (__bf16)e;
-            }
+        for (int i = 0; i < 8; i += 2) {
+            const float e0 = __builtin_amdgcn_exp2f(__builtin_fmaf(st[rb][8 * t + i], c, -mc));
+            const float e1 = __builtin_amdgcn_exp2f(__builtin_fmaf(st[rb][8 * t + i + 1], c, -mc));
+            bf16x2 pr;
+            pr[0] = (__bf16)e0;
+            pr[1] = (__bf16)e1;
+            pb[g][i] = pr[0];
+            pb[g][i + 1] = pr[1];
+            if (i & 2) rs1 = __builtin_amdgcn_fdot2_f32_bf16(pr, ones, rs1, false);
+            else rs0 = __builtin_amdgcn_fdot2_f32_bf16(pr, ones, rs0, false);
         }
     }
     st_.l += rs0 + rs1;
@@ -744,7 +730,7 @@ __device__ __forceinline__ void dense_item(const AttnParams& p, char* lds, int b
     typedef Geo<D> G;
     typedef TileItems<D> TI;
     constexpr int NW = 8, KS = D / 16, DB = D / 32;
-    constexpr int LPT = 2 * G::LOADS / NW;        // copy instructions per wavefront per tile (K + V)
+    constexpr int LPT = 2 * G::LOADS / NW;        // copy instructions per wavefront per tile (K + V), all copying
     auto k_stage = [&](int t) -> char* { return lds + (t & 3) * G::TILE_BYTES; };
     auto v_stage = [&](int t) -> char* { return lds + (4 + (t & 3)) * G::TILE_BYTES; };
 
@@ -814,24 +800,57 @@ __device__ __forceinline__ void dense_item(const AttnParams& p, char* lds, int b
     items_run<D, TI::NPV, TI::NI>(ctx, pb, qf, acc, st);   // S_0
     mask_tail(st, 0, kv_len, h);
 
+    // Where the tile copies are issued.  At D = 128 the A phase is the critical one (measured per
+    // phase: the copy instructions cost it ~270 cycles while the B phase had ~550 cycles of
+    // slack), so the copies go to the start of the B phases, split between the groups: in its
+    // B(j) group 0 copies K_{j+3} and group 1 copies V_{j+3}.  With b(n) the n-th barrier of the
+    // loop, group 0 runs B(j) after b(2j+1) and A(j) after b(2j+2), group 1 one barrier later.
+    //   K_{j+3} overwrites K_{j-1}, last read by S_{j-1} = K_{j-1} Q^T in A(j-2) (both groups are
+    //   through it before b(2j)); K_t is first read in group 0's A(t-1) after b(2t): group 0
+    //   waits for its K_{j+1} at the end of B(j), before b(2j+2).
+    //   V_{j+3} overwrites V_{j-1}, last read in group 1's A(j-1) (done before b(2j+2)); V_t is
+    //   first read in group 0's B(t) after b(2t+1), the barrier that ends group 1's B(t-1):
+    //   group 1 waits for its V_{j+1} at the end of B(j).
+    // At D = 64 the B phase is the longer one and every wavefront issues its share of tile j+3
+    // at the start of A(j).
+    constexpr bool COPY_IN_B = (D == 128);
+    constexpr int LC = G::LOADS / 4;              // copy instructions per wavefront for one K or V tile by one group
     for (int j = 0; j < T; ++j) {
-        // my share of tile j+1 (outstanding: tiles j+1 and j+2, completing in order)
-        if (j + 2 < T) wait_vmcnt<LPT>();
-        else wait_vmcnt<0>();
+        if constexpr (!COPY_IN_B) {
+            // my share of tile j+1 (outstanding: tiles j+1 and j+2, completing in order)
+            if (j + 2 < T) wait_vmcnt<LPT>();
+            else wait_vmcnt<0>();
+        }
         phase_barrier();
 
         // ---- B(j)
+        if constexpr (COPY_IN_B) {
+            if (j + 3 < T) {
+                if (group == 0) issue_tile<D, 4, false>(K, (j + 3) * KT, kv_len, k_stage(j + 3), wave, lane);
+                else issue_tile<D, 4, true>(V, (j + 3) * KT, kv_len, v_stage(j + 3), wave - 4, lane);
+            }
+        }
         v_addresses<D>(v_stage(j), h, tr_row, tr_col, ctx.vaddr);
         softmax_tile<D>(st, acc, sm, p.c, tau, pb);
         pin_in_phase(pb, sm.l);
         items_prefetch<D, 0, TI::NI>(ctx);        // first V_j^T fragments of A(j)
+        if constexpr (COPY_IN_B) {
+            // my group's tile j+1 has landed; its tiles j+2 and j+3 may still be on their way
+            // (tiles 0..2 came with the prologue: in the loop tile t is issued in B(t-3))
+            const int newer = ((j >= 1 && j + 2 < T) ? 1 : 0) + ((j + 3 < T) ? 1 : 0);
+            if (newer == 2) wait_vmcnt<2 * LC>();
+            else if (newer == 1) wait_vmcnt<LC>();
+            else wait_vmcnt<0>();
+        }
         phase_barrier();
 
         // ---- A(j): matrix work first in line at the SIMD's issue arbiter
         __builtin_amdgcn_s_setprio(3);
-        if (j + 3 < T) {
-            issue_tile<D, NW, false>(K, (j + 3) * KT, kv_len, k_stage(j + 3), wave, lane);
-            issue_tile<D, NW, true>(V, (j + 3) * KT, kv_len, v_stage(j + 3), wave, lane);
+        if constexpr (!COPY_IN_B) {
+            if (j + 3 < T) {
+                issue_tile<D, NW, false>(K, (j + 3) * KT, kv_len, k_stage(j + 3), wave, lane);
+                issue_tile<D, NW, true>(V, (j + 3) * KT, kv_len, v_stage(j + 3), wave, lane);
+            }
         }
         // PV(j) then QK(j+1) as one stream.  For the last tile the QK half re-reads a
         // landed stage and its result is never used.
