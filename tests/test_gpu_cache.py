@@ -42,7 +42,8 @@ def tensors(shape, seed, special=True):
     return x, y
 
 
-SHAPES = [(1, 8), (1, 1), (1, 7), (1, 4099), (3, 40), (2, 4096), (5, 1001), (4, 16, 12, 8), (1, 300001), (8, 65536)]
+SHAPES = [(1, 8), (1, 1), (1, 7), (1, 4099), (3, 40), (2, 4096), (5, 1001), (4, 16, 12, 8), (1, 300001), (8, 65536),
+          (1, 4608 * 3072)]          # the last: one layer's hidden states, the size bench.py times
 
 
 @pytest.mark.parametrize("shape", SHAPES, ids=[str(s) for s in SHAPES])

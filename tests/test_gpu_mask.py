@@ -43,6 +43,7 @@ CASES = [
     (2, 2, 4608, 128, 128, 4608, 4096, 2.5),
     (1, 3, 4480, 64, 128, 4429, 4096, 3.0),
     (1, 1, 8192, 64, 64, 8192, 9000, 3.0),      # 128 blocks per row: two per lane
+    (1, 2, 16896, 128, 128, 16896, 16384, 2.5), # the 2048^2 FLUX-like shape: 132 blocks per side
 ]
 
 
