@@ -142,23 +142,49 @@ constexpr int PLAN_BINS = 8192;                  // 8 bins per thread
 
 constexpr int PLAN_CACHE = 4096;                 // counts of this many items are kept in LDS
 
-// Exclusive prefix sum of one value per thread over the 1024 threads of the block: a shuffle
-// scan inside each wavefront, then the 16 wavefront totals through LDS.  Two barriers.
+// Inclusive prefix sum over the 64 lanes of a wavefront with data-parallel-primitive moves:
+// four shifts inside each row of 16 lanes, then lane 15 of rows 0 and 2 is added to rows 1
+// and 3, then lane 31 to rows 2 and 3.  A lane without a source takes 0.  All lanes active.
+__device__ __forceinline__ int wave_scan_inclusive(int v)
+{
+    v += __builtin_amdgcn_update_dpp(0, v, 0x111, 0xf, 0xf, false);   // row_shr:1
+    v += __builtin_amdgcn_update_dpp(0, v, 0x112, 0xf, 0xf, false);   // row_shr:2
+    v += __builtin_amdgcn_update_dpp(0, v, 0x114, 0xf, 0xf, false);   // row_shr:4
+    v += __builtin_amdgcn_update_dpp(0, v, 0x118, 0xf, 0xf, false);   // row_shr:8
+    v += __builtin_amdgcn_update_dpp(0, v, 0x142, 0xa, 0xf, false);   // row_bcast:15 into rows 1, 3
+    v += __builtin_amdgcn_update_dpp(0, v, 0x143, 0xc, 0xf, false);   // row_bcast:31 into rows 2, 3
+    return v;
+}
+
+// Exclusive prefix sum of one value per thread over the 1024 threads of the block: a scan
+// inside each wavefront, then the 16 wavefront totals through LDS.  Two barriers.
 __device__ __forceinline__ int plan_block_scan(int v, int* wave_sum, int tid)
 {
     const int lane = tid & 63, wv = tid >> 6;
-    int incl = v;
-#pragma unroll
-    for (int d = 1; d < 64; d <<= 1) {
-        const int t = __shfl_up(incl, d, 64);
-        if (lane >= d) incl += t;
-    }
+    const int incl = wave_scan_inclusive(v);
     if (lane == 63) wave_sum[wv] = incl;
     __syncthreads();
     int before = 0;
-    for (int w = 0; w < wv; ++w) before += wave_sum[w];
+#pragma unroll
+    for (int w = 0; w < 16; ++w) {                // all 16 reads in flight, none depends on wv
+        const int t = wave_sum[w];
+        before += w < wv ? t : 0;
+    }
     __syncthreads();
     return before + incl - v;
+}
+
+// Sum of one value per thread over the 1024 threads of the block, to every thread.  Two barriers.
+__device__ __forceinline__ int plan_block_total(int v, int* wave_sum, int tid)
+{
+    const int incl = wave_scan_inclusive(v);
+    if ((tid & 63) == 63) wave_sum[tid >> 6] = incl;
+    __syncthreads();
+    int sum = 0;
+#pragma unroll
+    for (int w = 0; w < 16; ++w) sum += wave_sum[w];
+    __syncthreads();
+    return sum;
 }
 
 // Exclusive prefix sum of hist[0 .. PLAN_BINS) in place (thread t owns bins 8t..8t+7).
@@ -324,6 +350,165 @@ __global__ __launch_bounds__(1024) void plan_split_kernel(const int32_t* __restr
             }
         }
     }
+}
+
+// Small problems (the 1024x1024-image shapes: about a hundred items per XCD): compaction and
+// plan in ONE launch, written for latency.  Two launches with a trip through memory between
+// them cost 11 us of a sparse call that takes 80 .. 130 us.  Here every thread loads its
+// bytes of the XCD's mask rows at once and keeps them in registers; a kept block sets its
+// bit in the row's 64-bit word in LDS (nb <= 64), the rank of a block in its row's list is a
+// population count below its bit, and the plan is made one thread per item in 32-bit
+// arithmetic (same rule, same records as plan_split_kernel: the limits below keep every
+// intermediate below 2^32).  No loop in it depends on memory more than once.
+constexpr int SMALL_NB = 64;                     // mask blocks per side
+constexpr int SMALL_ITEMS = 1024;                // items of one XCD
+constexpr int SMALL_SWEEPS = 8;                  // mask bytes of one XCD's items: 1024 per sweep
+constexpr int SMALL_BYTES = 1024 * SMALL_SWEEPS;
+
+__global__ __launch_bounds__(1024) void plan_small_kernel(
+    const unsigned char* __restrict__ mask, const int32_t* __restrict__ kv_lens, int kv_len, int N, int block,
+    int H, int BH, int nb, int cap, int pmax,
+    int32_t* __restrict__ counts, int32_t* __restrict__ index, PlanRec* __restrict__ recs,
+    int32_t* __restrict__ arrived)
+{
+    __shared__ unsigned rowbits[2 * SMALL_ITEMS]; // kept key-blocks of item i: bits of words 2i, 2i+1
+    __shared__ int live[SMALL_ITEMS];            // per (b,h) pair: key-blocks that start below kv_len
+    __shared__ int hist[128];                    // by r = nb - length; hist[nb + 1] = number of records
+    __shared__ int wave_sum[16];
+    const int x = blockIdx.x, tid = threadIdx.x;
+    const int n_bh = BH > x ? (BH - x + XCDS - 1) / XCDS : 0;
+    const int n_items = n_bh * nb;
+    const unsigned per_bh = (unsigned)(nb * nb);
+    const unsigned bytes = (unsigned)n_bh * per_bh;
+    PlanRec* out = recs + (size_t)x * cap;
+    // f / nb^2 for f * nb^2 < 2^32 by one multiplication (nb = 1: the product wraps, handled
+    // apart); f / nb for f < 2^13, nb <= 64 by a full-rate 24-bit multiplication: with
+    // m = ceil(2^19 / nb), f * (m * nb - 2^19) < 2^13 * 64 = 2^19, so the quotient is exact
+    const unsigned magic_bh = 0xffffffffu / per_bh + 1u, magic_nb = ((1u << 19) + (unsigned)nb - 1u) / (unsigned)nb;
+    auto div_bh = [&](unsigned f) { return per_bh == 1u ? f : __umulhi(f, magic_bh); };
+    auto div_nb = [&](unsigned f) { return __umul24(f, magic_nb) >> 19; };
+
+    // byte f of this XCD's rows: pair g = f / nb^2, then row-major inside the pair.  Lanes past
+    // the end load the last byte again, so that no load sits behind a branch.
+    unsigned v[SMALL_SWEEPS];
+#pragma unroll
+    for (int t = 0; t < SMALL_SWEEPS; ++t) {
+        v[t] = 0;
+        if (1024u * t < bytes) {                  // the same for the whole workgroup
+            const unsigned f = (unsigned)tid + 1024u * t, fc = f < bytes ? f : bytes - 1u;
+            const unsigned g = div_bh(fc);
+            v[t] = mask[(size_t)(g * XCDS + x) * per_bh + (fc - g * per_bh)];
+        }
+    }
+    for (int g = tid; g < n_bh; g += 1024) {
+        int len = kv_len;
+        if (kv_lens != nullptr) {
+            len = kv_lens[(g * XCDS + x) / H];
+            len = len < 0 ? 0 : (len > N ? N : len);
+        }
+        const int lv = (len + block - 1) / block;
+        live[g] = lv < nb ? lv : nb;
+    }
+    for (int i = tid; i < pmax; i += 1024) arrived[(size_t)x * pmax + i] = 0;
+    rowbits[tid] = 0u;
+    rowbits[tid + 1024] = 0u;
+    if (tid < 128) hist[tid] = 0;
+    __syncthreads();
+
+    // 64 consecutive bytes are the ends of at most a few rows: one ballot, and the first lane
+    // of each row's stretch adds the stretch to the row's word (same-address LDS atomics from
+    // every lane would serialise)
+#pragma unroll
+    for (int t = 0; t < SMALL_SWEEPS; ++t) {
+        if (1024u * t < bytes) {                  // the same for the whole workgroup
+            const unsigned f = (unsigned)tid + 1024u * t;
+            const bool in = f < bytes;
+            const unsigned i = div_nb(in ? f : 0u), j = (in ? f : 0u) - __umul24(i, nb);
+            const bool keep = in && v[t] != 0u && (int)j < live[div_nb(i)];
+            const unsigned long long bal = __ballot(keep);
+            const unsigned lane = (unsigned)tid & 63u;
+            if (in && (j == 0u || lane == 0u)) {
+                const unsigned left = (unsigned)nb - j, room = 64u - lane;
+                const unsigned len = left < room ? left : room;
+                const unsigned long long seg = (bal >> lane) & (len >= 64u ? ~0ull : (1ull << len) - 1ull);
+                const unsigned long long word = seg << j;                      // j + len <= nb <= 64
+                if ((unsigned)word) atomicOr(&rowbits[2u * i], (unsigned)word);
+                if ((unsigned)(word >> 32)) atomicOr(&rowbits[2u * i + 1u], (unsigned)(word >> 32));
+            }
+        }
+    }
+    __syncthreads();
+
+#pragma unroll
+    for (int t = 0; t < SMALL_SWEEPS; ++t) {
+        const unsigned f = (unsigned)tid + 1024u * t;
+        if (f < bytes && v[t] != 0u) {
+            const unsigned i = div_nb(f), j = f - __umul24(i, nb), g = div_nb(i);
+            const unsigned lo = rowbits[2u * i], hi = rowbits[2u * i + 1u];
+            const unsigned long long bits = ((unsigned long long)hi << 32) | lo;
+            if ((bits >> j) & 1ull) {
+                const unsigned row = __umul24(g * XCDS + x, nb) + (i - __umul24(g, nb));   // < 2^13
+                index[__umul24(row, nb) + __popcll(bits & ((1ull << j) - 1ull))] = (int)j;
+            }
+        }
+    }
+
+    // plan: thread i takes item i.  Pieces as in split_pieces(), in 32 bits.
+    const bool has = tid < n_items;
+    const int item = has ? (int)(__umul24(div_nb(tid) * XCDS + x, nb) + (tid - __umul24(div_nb(tid), nb))) : 0;
+    const int c = has ? __popc(rowbits[2 * tid]) + __popc(rowbits[2 * tid + 1]) : 0;
+    if (has) counts[item] = c;
+    const unsigned tot = (unsigned)plan_block_total(c, wave_sum, tid);
+    int want = 1;
+    if (has && tot != 0u) {
+        unsigned P = (2u * (unsigned)c * (CUS_PER_XCD * SPLIT_PER_CU) + tot) / (2u * tot);
+        const unsigned by_len = (unsigned)c / SPLIT_MIN_BLOCKS;
+        P = P > by_len ? by_len : P;
+        P = P > (unsigned)SPLIT_MAX_PIECES ? SPLIT_MAX_PIECES : P;
+        want = P < 1u ? 1 : (int)P;
+    }
+    const int first_slot = plan_block_scan(want > 1 ? want : 0, wave_sum, tid);
+    int P = want, slot0 = -1;
+    if (want > 1) {
+        if (first_slot + want <= pmax) slot0 = first_slot; else P = 1;
+    }
+    // piece k holds c(k+1)/P - ck/P key-blocks: c/P, plus one whenever the running remainder wraps
+    const int q = c / P, r = c - q * P;
+    if (has) {
+        int e = 0;
+        for (int k = 0; k < P; ++k) {
+            e += r;
+            const int extra = e >= P;
+            e -= extra ? P : 0;
+            atomicAdd(&hist[nb - (q + extra)], 1);
+        }
+    }
+    __syncthreads();
+    {
+        const int mine = tid <= nb ? hist[tid] : 0;
+        const int before = plan_block_scan(mine, wave_sum, tid);
+        if (tid <= nb + 1) hist[tid] = before;   // entry nb + 1: all records
+    }
+    __syncthreads();
+    const int n_rec = hist[nb + 1];
+    __syncthreads();                              // everyone has read it before the bins move
+    if (has) {
+        int e = 0, b0 = 0;
+        for (int k = 0; k < P; ++k) {
+            e += r;
+            const int extra = e >= P;
+            e -= extra ? P : 0;
+            PlanRec rec;
+            rec.item = item;
+            rec.blk0 = b0;
+            rec.nblk = q + extra;
+            rec.w = (P > 1) ? (((x * pmax + slot0) << 8) | (k << 4) | (P - 1)) : -1;
+            b0 += rec.nblk;
+            out[atomicAdd(&hist[nb - rec.nblk], 1)] = rec;
+        }
+    }
+    const PlanRec none = {-1, 0, 0, -1};
+    for (int i = n_rec + tid; i < cap; i += 1024) out[i] = none;
 }
 
 // ---------------------------------------------------------------------------
@@ -1404,14 +1589,21 @@ int run_sparse(const Problem& pr, int block, const unsigned char* mask, void* wo
     int32_t* index = (int32_t*)(ws + w.index_off);
     hipStream_t s = (hipStream_t)stream;
 
-    hipLaunchKernelGGL(compact_mask_kernel, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, s,
-                       mask, (int)rows, nb, block, pr.kv_len, pr.kv_lens, H * nb, N, counts, index);
-    if (hipGetLastError() != hipSuccess) return RAPID_ERR_DEVICE;
-    if (block == 128)
-        hipLaunchKernelGGL(plan_split_kernel, dim3(XCDS), dim3(1024), 0, s, counts, B * H, nb, w.chunk,
-                           w.pmax, (PlanRec*)order, (int32_t*)(ws + w.arrived_off));
-    else
-        hipLaunchKernelGGL(plan_kernel, dim3(XCDS), dim3(1024), 0, s, counts, B * H, nb, w.chunk, order);
+    const int xcd_items = plan_items(B, H, nb);
+    if (block == 128 && nb <= SMALL_NB && xcd_items <= SMALL_ITEMS && xcd_items * nb <= SMALL_BYTES) {
+        hipLaunchKernelGGL(plan_small_kernel, dim3(XCDS), dim3(1024), 0, s, mask, pr.kv_lens, pr.kv_len, N, block,
+                           H, B * H, nb, w.chunk, w.pmax, counts, index, (PlanRec*)order,
+                           (int32_t*)(ws + w.arrived_off));
+    } else {
+        hipLaunchKernelGGL(compact_mask_kernel, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, s,
+                           mask, (int)rows, nb, block, pr.kv_len, pr.kv_lens, H * nb, N, counts, index);
+        if (hipGetLastError() != hipSuccess) return RAPID_ERR_DEVICE;
+        if (block == 128)
+            hipLaunchKernelGGL(plan_split_kernel, dim3(XCDS), dim3(1024), 0, s, counts, B * H, nb, w.chunk,
+                               w.pmax, (PlanRec*)order, (int32_t*)(ws + w.arrived_off));
+        else
+            hipLaunchKernelGGL(plan_kernel, dim3(XCDS), dim3(1024), 0, s, counts, B * H, nb, w.chunk, order);
+    }
     if (hipGetLastError() != hipSuccess) return RAPID_ERR_DEVICE;
 
     AttnParams p{};

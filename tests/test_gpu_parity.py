@@ -221,6 +221,42 @@ def test_compaction_is_bit_exact_with_64_token_tiles():
     check_plan(counts, order, g, B, H, nb, block)
 
 
+PLANNERS = [
+    # B, H, N, kv_len, p_keep: 128-token tiles, D = 64.  Up to 64 blocks per side, 1024 items and
+    # 8 KB of mask rows per XCD the one-launch planner runs, beyond that compaction + planner.
+    (1, 3, 128, 100, 1.0),        # one block per side, XCDs 3..7 without items
+    (1, 2, 8192, 8100, 0.3),      # 64 blocks per side: a row fills the whole 64-bit word
+    (2, 8, 8192, 8192, 0.2),      # two pairs per XCD: exactly 8 KB of mask rows
+    (3, 8, 8192, 8000, 0.2),      # three pairs per XCD: past the limit
+    (1, 8, 10240, 10200, 0.25),   # 80 blocks per side: past the limit
+    (37, 3, 640, 520, 0.6),       # 111 pairs: 14 per XCD on some, 13 on others
+]
+
+
+@pytest.mark.parametrize("B,H,N,kv_len,p", PLANNERS)
+def test_lists_and_plan_on_both_planners(B, H, N, kv_len, p):
+    """Kept-block lists against the oracle's and the launch plan record for record, on shapes on
+    both sides of the limits that choose between the two planners (the outputs themselves are
+    compared with the oracle in the other tests; here a few sampled rows)."""
+    D, block = 64, 128
+    nb = N // block
+    q, k, v = wl.make_qkv(B, H, N, D, kv_len, seed=B * 1000 + nb)
+    mask = wl.mask_bernoulli_diag(B, H, nb, p, seed=nb)
+    mask[0, 0, nb // 2, :] = 0                              # an empty row
+    mask[-1, -1, 0, :] = 7                                  # a full row, nonzero but not 1
+    got, ws = run_sparse(q, k, v, mask, block, kv_len, return_ws=True)
+    counts, order, index, g = read_plan(ws, B, H, nb, D, block)
+    want_counts, want_index = oracle.kept_tiles(mask, block, kv_len)
+    np.testing.assert_array_equal(counts, want_counts.reshape(-1))
+    want_index = want_index.reshape(-1, nb)
+    for r in range(B * H * nb):
+        np.testing.assert_array_equal(index[r, :counts[r]], want_index[r, :counts[r]])
+    check_plan(counts, order, g, B, H, nb, block)
+    rows = wl.sample_rows(B, H, N, kv_len, block, 48, seed=5)
+    ref = oracle.attention_rows(q, k, v, rows, kv_len, mask, block)
+    assert_close(got[rows[:, 0], rows[:, 1], rows[:, 2]], ref, "sampled rows")
+
+
 @pytest.mark.parametrize("D", [64, 128])
 def test_long_rows_are_split_into_pieces_and_merged(D):
     """A few rows keep every tile while the rest keep few: the long rows are cut into pieces
