@@ -174,19 +174,6 @@ __device__ __forceinline__ int plan_block_scan(int v, int* wave_sum, int tid)
     return before + incl - v;
 }
 
-// Sum of one value per thread over the 1024 threads of the block, to every thread.  Two barriers.
-__device__ __forceinline__ int plan_block_total(int v, int* wave_sum, int tid)
-{
-    const int incl = wave_scan_inclusive(v);
-    if ((tid & 63) == 63) wave_sum[tid >> 6] = incl;
-    __syncthreads();
-    int sum = 0;
-#pragma unroll
-    for (int w = 0; w < 16; ++w) sum += wave_sum[w];
-    __syncthreads();
-    return sum;
-}
-
 // Exclusive prefix sum of hist[0 .. PLAN_BINS) in place (thread t owns bins 8t..8t+7).
 __device__ __forceinline__ void plan_scan_bins(int* hist, int* wave_sum, int tid)
 {
@@ -374,7 +361,7 @@ __global__ __launch_bounds__(1024) void plan_small_kernel(
     __shared__ unsigned rowbits[2 * SMALL_ITEMS]; // kept key-blocks of item i: bits of words 2i, 2i+1
     __shared__ int live[SMALL_ITEMS];            // per (b,h) pair: key-blocks that start below kv_len
     __shared__ int hist[128];                    // by r = nb - length; hist[nb + 1] = number of records
-    __shared__ int wave_sum[16];
+    __shared__ int wave_sum[16], kept_sum[16];
     const int x = blockIdx.x, tid = threadIdx.x;
     const int n_bh = BH > x ? (BH - x + XCDS - 1) / XCDS : 0;
     const int n_items = n_bh * nb;
@@ -418,6 +405,7 @@ __global__ __launch_bounds__(1024) void plan_small_kernel(
     // 64 consecutive bytes are the ends of at most a few rows: one ballot, and the first lane
     // of each row's stretch adds the stretch to the row's word (same-address LDS atomics from
     // every lane would serialise)
+    int kept = 0;                                 // kept blocks seen by this wavefront
 #pragma unroll
     for (int t = 0; t < SMALL_SWEEPS; ++t) {
         if (1024u * t < bytes) {                  // the same for the whole workgroup
@@ -427,6 +415,7 @@ __global__ __launch_bounds__(1024) void plan_small_kernel(
             const bool keep = in && v[t] != 0u && (int)j < live[div_nb(i)];
             const unsigned long long bal = __ballot(keep);
             const unsigned lane = (unsigned)tid & 63u;
+            kept += __popcll(bal);
             if (in && (j == 0u || lane == 0u)) {
                 const unsigned left = (unsigned)nb - j, room = 64u - lane;
                 const unsigned len = left < room ? left : room;
@@ -437,7 +426,11 @@ __global__ __launch_bounds__(1024) void plan_small_kernel(
             }
         }
     }
+    if ((tid & 63) == 0) kept_sum[tid >> 6] = kept;
     __syncthreads();
+    unsigned tot = 0u;                            // kept key-blocks of this XCD's items
+#pragma unroll
+    for (int w = 0; w < 16; ++w) tot += (unsigned)kept_sum[w];
 
 #pragma unroll
     for (int t = 0; t < SMALL_SWEEPS; ++t) {
@@ -458,7 +451,6 @@ __global__ __launch_bounds__(1024) void plan_small_kernel(
     const int item = has ? (int)(__umul24(div_nb(tid) * XCDS + x, nb) + (tid - __umul24(div_nb(tid), nb))) : 0;
     const int c = has ? __popc(rowbits[2 * tid]) + __popc(rowbits[2 * tid + 1]) : 0;
     if (has) counts[item] = c;
-    const unsigned tot = (unsigned)plan_block_total(c, wave_sum, tid);
     int want = 1;
     if (has && tot != 0u) {
         unsigned P = (2u * (unsigned)c * (CUS_PER_XCD * SPLIT_PER_CU) + tot) / (2u * tot);
