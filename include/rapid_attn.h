@@ -101,11 +101,12 @@ RAPID_API int rapid_attn_dense(const void* q, const void* k, const void* v, void
  *                          (-1,0,0,-1).  w = -1 for a whole item.  An item
  *                          with c kept blocks, in an XCD whose items keep
  *                          `total` blocks, is cut into
- *                          P = max(1, min(round(c*192/total), c/8, 16))
- *                          pieces [c*k/P, c*(k+1)/P) (192 = 32 CUs x 6:
- *                          pieces of about a sixth of a CU's share, at
- *                          least 8 key-blocks each) whose partial results
- *                          are added up in piece order;
+ *                          P = max(1, min(round(c*g/total), c/8, 16))
+ *                          pieces [c*k/P, c*(k+1)/P), g = 32 CUs x 3 at
+ *                          D = 128 and 32 x 12 at D = 64 (pieces of about
+ *                          a third / a twelfth of a CU's share, at least
+ *                          8 key-blocks each), whose partial results are
+ *                          added up in piece order;
  *                          w = (slot << 8) | (k << 4) | (P-1), the slots
  *                          (pmax = min(256, items) per XCD) handed out in
  *                          item order; an item that no longer fits stays

@@ -215,14 +215,18 @@ __global__ __launch_bounds__(1024) void plan_kernel(const int32_t* __restrict__ 
 }
 
 // 128-token mask tiles: the plan is a list of records, one per workgroup.  The dispatcher
-// fills the CUs entry by entry, so the entries have to be small against a CU's share of the
-// work or the last ones leave most of the chip idle: an item is cut into P pieces of about
-// 1/SPLIT_PER_CU of that share (kept key-blocks of the XCD / its CUs), but of at least
-// SPLIT_MIN_BLOCKS key-blocks each so that the fixed cost of an entry stays small, and into at
-// most SPLIT_MAX_PIECES.  Each piece is a record of its own; the pieces leave partial results
-// in the workspace and the last one to finish combines them.  Partial-result slots are
-// handed out in item order (a prefix sum, so the plan does not depend on timing); an item
-// that no longer fits in the XCD's pmax slots stays whole.
+// fills the CUs entry by entry, so an entry that is long against a CU's share of the work
+// leaves most of the chip idle at the end: an item is cut into P pieces of about 1/per_cu
+// of that share (kept key-blocks of the XCD / its CUs), but of at least SPLIT_MIN_BLOCKS
+// key-blocks each, and into at most SPLIT_MAX_PIECES.  Each piece is a record of its own;
+// the pieces leave partial results in the workspace and the last one to finish combines
+// them.  A piece is expensive (its partial result goes through memory: measured, an entry
+// costs about two key-blocks of time and a piece two more), so per_cu is small: 3 at
+// D = 128, where two workgroups share a CU and only rows several times the average (the
+// text rows of a sparse mask) are worth cutting; 12 at D = 64, where four share it and an
+// all-ones mask has fewer items than the chip has places.  Partial-result slots are handed
+// out in item order (a prefix sum, so the plan does not depend on timing); an item that no
+// longer fits in the XCD's pmax slots stays whole.
 struct PlanRec {
     int item;     // b*H*nb + h*nb + query-block, or -1: no work
     int blk0;     // first position of the piece in the item's kept list
@@ -230,16 +234,16 @@ struct PlanRec {
     int w;        // -1: the whole item; else (first partial slot << 8) | (piece << 4) | (P - 1)
 };
 constexpr int CUS_PER_XCD = 32;                  // MI355X: 256 CUs in 8 XCDs
-constexpr int SPLIT_PER_CU = 6;
+__host__ __device__ constexpr int split_per_cu(int D) { return D == 128 ? 3 : 12; }
 constexpr int SPLIT_MIN_BLOCKS = 8;
 constexpr int SPLIT_MAX_PIECES = 16;
 constexpr int SPLIT_SLOTS = 256;                 // partial-result slots per XCD (the rule needs < 256)
 
-// P = round(c / target), target = total / (CUS_PER_XCD * SPLIT_PER_CU), within the limits above
-__device__ __forceinline__ int split_pieces(int c, unsigned long long total)
+// P = round(c / target), target = total / (CUS_PER_XCD * per_cu), within the limits above
+__device__ __forceinline__ int split_pieces(int c, unsigned long long total, int per_cu)
 {
     if (total == 0ull) return 1;
-    const unsigned long long g = (unsigned long long)CUS_PER_XCD * SPLIT_PER_CU;
+    const unsigned long long g = (unsigned long long)(CUS_PER_XCD * per_cu);
     unsigned long long P = (2ull * (unsigned)c * g + total) / (2ull * total);
     const unsigned long long by_len = (unsigned)c / SPLIT_MIN_BLOCKS;
     if (P > by_len) P = by_len;
@@ -248,7 +252,7 @@ __device__ __forceinline__ int split_pieces(int c, unsigned long long total)
 }
 
 __global__ __launch_bounds__(1024) void plan_split_kernel(const int32_t* __restrict__ counts, int BH, int nb, int cap,
-                                                          int pmax, PlanRec* __restrict__ recs,
+                                                          int pmax, int per_cu, PlanRec* __restrict__ recs,
                                                           int32_t* __restrict__ arrived)
 {
     __shared__ int hist[PLAN_BINS];              // by r = nb - length (r = 0: longest)
@@ -295,13 +299,13 @@ __global__ __launch_bounds__(1024) void plan_split_kernel(const int32_t* __restr
     const int hi = lo + per < n_items ? lo + per : n_items;
     int mine = 0;
     for (int i = lo; i < hi; ++i) {
-        const int P = split_pieces(count_of(i), tot);
+        const int P = split_pieces(count_of(i), tot, per_cu);
         if (P > 1) mine += P;
     }
     const int first_slot = plan_block_scan(mine, wave_sum, tid);
     // pieces of item i: P (1 = whole) and the first partial slot
     auto pieces_of = [&](int c, int& run, int& P, int& slot0) {
-        const int want = split_pieces(c, tot);
+        const int want = split_pieces(c, tot, per_cu);
         P = want;
         slot0 = -1;
         if (want > 1) {
@@ -354,7 +358,7 @@ constexpr int SMALL_BYTES = 1024 * SMALL_SWEEPS;
 
 __global__ __launch_bounds__(1024) void plan_small_kernel(
     const unsigned char* __restrict__ mask, const int32_t* __restrict__ kv_lens, int kv_len, int N, int block,
-    int H, int BH, int nb, int cap, int pmax,
+    int H, int BH, int nb, int cap, int pmax, int per_cu,
     int32_t* __restrict__ counts, int32_t* __restrict__ index, PlanRec* __restrict__ recs,
     int32_t* __restrict__ arrived)
 {
@@ -453,7 +457,7 @@ __global__ __launch_bounds__(1024) void plan_small_kernel(
     if (has) counts[item] = c;
     int want = 1;
     if (has && tot != 0u) {
-        unsigned P = (2u * (unsigned)c * (CUS_PER_XCD * SPLIT_PER_CU) + tot) / (2u * tot);
+        unsigned P = (2u * (unsigned)c * (unsigned)(CUS_PER_XCD * per_cu) + tot) / (2u * tot);
         const unsigned by_len = (unsigned)c / SPLIT_MIN_BLOCKS;
         P = P > by_len ? by_len : P;
         P = P > (unsigned)SPLIT_MAX_PIECES ? SPLIT_MAX_PIECES : P;
@@ -1584,7 +1588,7 @@ int run_sparse(const Problem& pr, int block, const unsigned char* mask, void* wo
     const int xcd_items = plan_items(B, H, nb);
     if (block == 128 && nb <= SMALL_NB && xcd_items <= SMALL_ITEMS && xcd_items * nb <= SMALL_BYTES) {
         hipLaunchKernelGGL(plan_small_kernel, dim3(XCDS), dim3(1024), 0, s, mask, pr.kv_lens, pr.kv_len, N, block,
-                           H, B * H, nb, w.chunk, w.pmax, counts, index, (PlanRec*)order,
+                           H, B * H, nb, w.chunk, w.pmax, split_per_cu(D), counts, index, (PlanRec*)order,
                            (int32_t*)(ws + w.arrived_off));
     } else {
         hipLaunchKernelGGL(compact_mask_kernel, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, s,
@@ -1592,7 +1596,7 @@ int run_sparse(const Problem& pr, int block, const unsigned char* mask, void* wo
         if (hipGetLastError() != hipSuccess) return RAPID_ERR_DEVICE;
         if (block == 128)
             hipLaunchKernelGGL(plan_split_kernel, dim3(XCDS), dim3(1024), 0, s, counts, B * H, nb, w.chunk,
-                               w.pmax, (PlanRec*)order, (int32_t*)(ws + w.arrived_off));
+                               w.pmax, split_per_cu(D), (PlanRec*)order, (int32_t*)(ws + w.arrived_off));
         else
             hipLaunchKernelGGL(plan_kernel, dim3(XCDS), dim3(1024), 0, s, counts, B * H, nb, w.chunk, order);
     }

@@ -140,15 +140,17 @@ def read_plan(ws, B, H, nb, D, block):
     return counts, order, index, g
 
 
-def split_pieces(c, total):
+def split_pieces(c, total, D):
     """Pieces of an item with c kept key-blocks when its XCD holds `total`: round(c / target) with
-    target = total / (32 CUs x 6), at most c // 8 (a piece has at least 8 key-blocks) and 16."""
+    target = total / (32 CUs x 3) at D = 128 and total / (32 x 12) at D = 64, at most c // 8 (a
+    piece has at least 8 key-blocks) and 16."""
     if total == 0:
         return 1
-    return max(1, min((2 * c * 192 + total) // (2 * total), c // 8, 16))
+    g = 32 * (3 if D == 128 else 12)
+    return max(1, min((2 * c * g + total) // (2 * total), c // 8, 16))
 
 
-def check_plan(counts, order, g, B, H, nb, block):
+def check_plan(counts, order, g, B, H, nb, block, D=64):
     """The launch plan, entry for entry.  Every XCD segment holds the entries of the (b,h) pairs
     with (b*H+h) % 8 == x, longest first, then -1.  With 64-token tiles an entry is an item; with
     128-token tiles it is a record (item, first list position, kept blocks, w) and an item that is
@@ -172,7 +174,7 @@ def check_plan(counts, order, g, B, H, nb, block):
         want, run = [], 0
         for it in mine:
             c = int(counts[it])
-            P = split_pieces(c, total)
+            P = split_pieces(c, total, D)
             slot0 = -1
             if P > 1:
                 if run + P <= g["pmax"]:
@@ -222,23 +224,25 @@ def test_compaction_is_bit_exact_with_64_token_tiles():
 
 
 PLANNERS = [
-    # B, H, N, kv_len, p_keep: 128-token tiles, D = 64.  Up to 64 blocks per side, 1024 items and
+    # B, H, N, kv_len, p_keep, D: 128-token tiles.  Up to 64 blocks per side, 1024 items and
     # 8 KB of mask rows per XCD the one-launch planner runs, beyond that compaction + planner.
-    (1, 3, 128, 100, 1.0),        # one block per side, XCDs 3..7 without items
-    (1, 2, 8192, 8100, 0.3),      # 64 blocks per side: a row fills the whole 64-bit word
-    (2, 8, 8192, 8192, 0.2),      # two pairs per XCD: exactly 8 KB of mask rows
-    (3, 8, 8192, 8000, 0.2),      # three pairs per XCD: past the limit
-    (1, 8, 10240, 10200, 0.25),   # 80 blocks per side: past the limit
-    (37, 3, 640, 520, 0.6),       # 111 pairs: 14 per XCD on some, 13 on others
+    (1, 3, 128, 100, 1.0, 64),        # one block per side, XCDs 3..7 without items
+    (1, 2, 8192, 8100, 0.3, 64),      # 64 blocks per side: a row fills the whole 64-bit word
+    (2, 8, 8192, 8192, 0.2, 128),     # two pairs per XCD: exactly 8 KB of mask rows
+    (3, 8, 8192, 8000, 0.2, 64),      # three pairs per XCD: past the limit
+    (1, 8, 10240, 10200, 0.25, 128),  # 80 blocks per side: past the limit
+    (37, 3, 640, 520, 0.6, 64),       # 111 pairs: 14 per XCD on some, 13 on others
+    (1, 24, 2816, 2816, 1.0, 128),    # all-ones mask with about as many items as the chip has places
 ]
 
 
-@pytest.mark.parametrize("B,H,N,kv_len,p", PLANNERS)
-def test_lists_and_plan_on_both_planners(B, H, N, kv_len, p):
+@pytest.mark.parametrize("B,H,N,kv_len,p,D", PLANNERS)
+def test_lists_and_plan_on_both_planners(B, H, N, kv_len, p, D):
     """Kept-block lists against the oracle's and the launch plan record for record, on shapes on
-    both sides of the limits that choose between the two planners (the outputs themselves are
-    compared with the oracle in the other tests; here a few sampled rows)."""
-    D, block = 64, 128
+    both sides of the limits that choose between the two planners and with both head sizes (the
+    split rule depends on it); the outputs themselves are compared with the oracle in the other
+    tests, here on a few sampled rows."""
+    block = 128
     nb = N // block
     q, k, v = wl.make_qkv(B, H, N, D, kv_len, seed=B * 1000 + nb)
     mask = wl.mask_bernoulli_diag(B, H, nb, p, seed=nb)
@@ -251,7 +255,7 @@ def test_lists_and_plan_on_both_planners(B, H, N, kv_len, p):
     want_index = want_index.reshape(-1, nb)
     for r in range(B * H * nb):
         np.testing.assert_array_equal(index[r, :counts[r]], want_index[r, :counts[r]])
-    check_plan(counts, order, g, B, H, nb, block)
+    check_plan(counts, order, g, B, H, nb, block, D)
     rows = wl.sample_rows(B, H, N, kv_len, block, 48, seed=5)
     ref = oracle.attention_rows(q, k, v, rows, kv_len, mask, block)
     assert_close(got[rows[:, 0], rows[:, 1], rows[:, 2]], ref, "sampled rows")
@@ -272,7 +276,7 @@ def test_long_rows_are_split_into_pieces_and_merged(D):
     got, ws = run_sparse(q, k, v, mask, block, kv_len, return_ws=True)
     counts, order, _, g = read_plan(ws, B, H, nb, D, block)
     np.testing.assert_array_equal(counts, oracle.kept_tiles(mask, block, kv_len)[0].reshape(-1))
-    assert check_plan(counts, order, g, B, H, nb, block) >= 2 * B * H
+    assert check_plan(counts, order, g, B, H, nb, block, D) >= 2 * B * H
     rng = np.random.default_rng(3)
     rows_ = np.stack([rng.integers(B, size=160), rng.integers(H, size=160),
                       rng.choice(np.r_[5 * block:6 * block, (nb - 1) * block:kv_len, 17 * block:18 * block,
