@@ -103,10 +103,14 @@ RAPID_API int rapid_attn_dense(const void* q, const void* k, const void* v, void
  *                          `total` blocks, is cut into
  *                          P = max(1, min(round(c*g/total), c/8, 16))
  *                          pieces [c*k/P, c*(k+1)/P), g = 32 CUs x 3 at
- *                          D = 128 and 32 x 12 at D = 64 (pieces of about
- *                          a third / a twelfth of a CU's share, at least
+ *                          D = 128 and 32 x 4 at D = 64 (pieces of about
+ *                          a third / a quarter of a CU's share, at least
  *                          8 key-blocks each), whose partial results are
- *                          added up in piece order;
+ *                          added up in piece order.  When the XCD's n rows
+ *                          are all alike (8 n max(c) <= 9 total): g =
+ *                          32 x 12 at D = 64; at D = 128 every item takes
+ *                          the first P in 1 .. max(c)/8 that minimises
+ *                          ceil(n P / 64) (ceil(max(c) / P) + 2 + 2 [P>1]);
  *                          w = (slot << 8) | (k << 4) | (P-1), the slots
  *                          (pmax = min(256, items) per XCD) handed out in
  *                          item order; an item that no longer fits stays

@@ -156,6 +156,19 @@ __device__ __forceinline__ int wave_scan_inclusive(int v)
     return v;
 }
 
+// Maximum over the 64 lanes, valid in lane 63 (same moves; a lane without a source keeps its own).
+__device__ __forceinline__ int wave_max_to_last(int v)
+{
+    auto step = [&](int t) { v = t > v ? t : v; };
+    step(__builtin_amdgcn_update_dpp(v, v, 0x111, 0xf, 0xf, false));
+    step(__builtin_amdgcn_update_dpp(v, v, 0x112, 0xf, 0xf, false));
+    step(__builtin_amdgcn_update_dpp(v, v, 0x114, 0xf, 0xf, false));
+    step(__builtin_amdgcn_update_dpp(v, v, 0x118, 0xf, 0xf, false));
+    step(__builtin_amdgcn_update_dpp(v, v, 0x142, 0xa, 0xf, false));
+    step(__builtin_amdgcn_update_dpp(v, v, 0x143, 0xc, 0xf, false));
+    return v;
+}
+
 // Exclusive prefix sum of one value per thread over the 1024 threads of the block: a scan
 // inside each wavefront, then the 16 wavefront totals through LDS.  Two barriers.
 __device__ __forceinline__ int plan_block_scan(int v, int* wave_sum, int tid)
@@ -216,17 +229,14 @@ __global__ __launch_bounds__(1024) void plan_kernel(const int32_t* __restrict__ 
 
 // 128-token mask tiles: the plan is a list of records, one per workgroup.  The dispatcher
 // fills the CUs entry by entry, so an entry that is long against a CU's share of the work
-// leaves most of the chip idle at the end: an item is cut into P pieces of about 1/per_cu
-// of that share (kept key-blocks of the XCD / its CUs), but of at least SPLIT_MIN_BLOCKS
-// key-blocks each, and into at most SPLIT_MAX_PIECES.  Each piece is a record of its own;
-// the pieces leave partial results in the workspace and the last one to finish combines
-// them.  A piece is expensive (its partial result goes through memory: measured, an entry
-// costs about two key-blocks of time and a piece two more), so per_cu is small: 3 at
-// D = 128, where two workgroups share a CU and only rows several times the average (the
-// text rows of a sparse mask) are worth cutting; 12 at D = 64, where four share it and an
-// all-ones mask has fewer items than the chip has places.  Partial-result slots are handed
-// out in item order (a prefix sum, so the plan does not depend on timing); an item that no
-// longer fits in the XCD's pmax slots stays whole.
+// leaves most of the chip idle at the end: an item can be cut into P pieces (SplitRule
+// below).  Each piece is a record of its own; the pieces leave partial results in the
+// workspace and the last one to finish combines them.  A piece is expensive (its partial
+// result goes through memory: measured at D = 128, an entry costs about two key-blocks of
+// time and a piece two more), so only rows several times the average (the text rows of a
+// sparse mask) are worth cutting.  Partial-result slots are handed out in item order (a
+// prefix sum, so the plan does not depend on timing); an item that no longer fits in the
+// XCD's pmax slots stays whole.
 struct PlanRec {
     int item;     // b*H*nb + h*nb + query-block, or -1: no work
     int blk0;     // first position of the piece in the item's kept list
@@ -234,17 +244,64 @@ struct PlanRec {
     int w;        // -1: the whole item; else (first partial slot << 8) | (piece << 4) | (P - 1)
 };
 constexpr int CUS_PER_XCD = 32;                  // MI355X: 256 CUs in 8 XCDs
-__host__ __device__ constexpr int split_per_cu(int D) { return D == 128 ? 3 : 12; }
 constexpr int SPLIT_MIN_BLOCKS = 8;
 constexpr int SPLIT_MAX_PIECES = 16;
 constexpr int SPLIT_SLOTS = 256;                 // partial-result slots per XCD (the rule needs < 256)
+constexpr int ENTRY_COST = 2, PIECE_COST = 2;    // measured, in key-blocks of time at D = 128
 
-// P = round(c / target), target = total / (CUS_PER_XCD * per_cu), within the limits above
-__device__ __forceinline__ int split_pieces(int c, unsigned long long total, int per_cu)
+// The rule of one XCD.  P(c) = round(c * g / total) pieces for an item with c kept key-blocks
+// (g granules: pieces of about total / g), or p_all pieces for every item when that is set;
+// in both cases at most c / SPLIT_MIN_BLOCKS and SPLIT_MAX_PIECES, at least 1.
+//   D = 128: g = 32 CUs x 3.  Rows that are all about alike (the longest within 1/9 of the
+//     mean: an all-ones mask) are not told apart by their lengths; what matters then is how
+//     many rounds the 64 places of the XCD need, so p_all is the P that minimises
+//     rounds(P) * (piece length + cost of an entry), the first such P.
+//   D = 64: g = 32 x 4; rows all alike: 32 x 12 (fewer items than the 128 places: cut them all).
+struct SplitRule {
+    int g;
+    int p_all;     // 0: by length
+};
+
+// cost of cutting every one of n_items rows of max_c blocks into P pieces, D = 128
+__device__ __forceinline__ long long split_alike_cost(int n_items, int max_c, int P)
+{
+    const long long places = CUS_PER_XCD * 2;
+    const long long rounds = ((long long)n_items * P + places - 1) / places;
+    return rounds * ((max_c + P - 1) / P + ENTRY_COST + (P > 1 ? PIECE_COST : 0));
+}
+
+__device__ __forceinline__ bool rows_alike(int n_items, int max_c, unsigned long long total)
+{
+    return 8ull * (unsigned long long)n_items * (unsigned)max_c <= 9ull * total;
+}
+
+// `costs` holds split_alike_cost for P = 1 .. SPLIT_MAX_PIECES (used at D = 128 when the rows are alike)
+__device__ __forceinline__ SplitRule split_rule(int D, int n_items, int max_c, unsigned long long total,
+                                                const long long* costs)
+{
+    SplitRule r;
+    r.p_all = 0;
+    const bool alike = rows_alike(n_items, max_c, total);
+    if (D == 128) {
+        r.g = CUS_PER_XCD * 3;
+        if (alike && total != 0ull) {
+            long long best = costs[0];
+            r.p_all = 1;
+            const int top = max_c / SPLIT_MIN_BLOCKS < SPLIT_MAX_PIECES ? max_c / SPLIT_MIN_BLOCKS : SPLIT_MAX_PIECES;
+            for (int P = 2; P <= top; ++P)
+                if (costs[P - 1] < best) { best = costs[P - 1]; r.p_all = P; }
+        }
+    } else {
+        r.g = CUS_PER_XCD * (alike ? 12 : 4);
+    }
+    return r;
+}
+
+__device__ __forceinline__ int split_pieces(int c, unsigned long long total, const SplitRule& rule)
 {
     if (total == 0ull) return 1;
-    const unsigned long long g = (unsigned long long)(CUS_PER_XCD * per_cu);
-    unsigned long long P = (2ull * (unsigned)c * g + total) / (2ull * total);
+    unsigned long long P = rule.p_all ? (unsigned long long)rule.p_all
+                                      : (2ull * (unsigned)c * (unsigned)rule.g + total) / (2ull * total);
     const unsigned long long by_len = (unsigned)c / SPLIT_MIN_BLOCKS;
     if (P > by_len) P = by_len;
     if (P > (unsigned long long)SPLIT_MAX_PIECES) P = SPLIT_MAX_PIECES;
@@ -252,13 +309,15 @@ __device__ __forceinline__ int split_pieces(int c, unsigned long long total, int
 }
 
 __global__ __launch_bounds__(1024) void plan_split_kernel(const int32_t* __restrict__ counts, int BH, int nb, int cap,
-                                                          int pmax, int per_cu, PlanRec* __restrict__ recs,
+                                                          int pmax, int D, PlanRec* __restrict__ recs,
                                                           int32_t* __restrict__ arrived)
 {
     __shared__ int hist[PLAN_BINS];              // by r = nb - length (r = 0: longest)
     __shared__ int ccache[PLAN_CACHE];           // counts of the first items, read once
     __shared__ int wave_sum[16];
     __shared__ unsigned long long total;          // kept key-blocks of this XCD's items
+    __shared__ int longest;                       // of its rows
+    __shared__ long long alike_cost[SPLIT_MAX_PIECES];
     const int x = blockIdx.x, tid = threadIdx.x;
     const int n_bh = (BH - x + XCDS - 1) / XCDS;
     const int n_items = n_bh > 0 ? n_bh * nb : 0;
@@ -275,37 +334,46 @@ __global__ __launch_bounds__(1024) void plan_split_kernel(const int32_t* __restr
         }
         return;
     }
-    if (tid == 0) total = 0ull;
+    if (tid == 0) { total = 0ull; longest = 0; }
 #pragma unroll
     for (int j = 0; j < 8; ++j) hist[8 * tid + j] = 0;
     __syncthreads();
     {
         unsigned long long mine = 0ull;
+        int mx = 0;
         for (int i = tid; i < n_items; i += 1024) {
             const int c = counts[item_of(i)];
             if (i < PLAN_CACHE) ccache[i] = c;
             mine += (unsigned long long)c;
+            mx = c > mx ? c : mx;
         }
 #pragma unroll
-        for (int d = 32; d >= 1; d >>= 1) mine += __shfl_down(mine, d, 64);
-        if ((tid & 63) == 0) atomicAdd(&total, mine);
+        for (int d = 32; d >= 1; d >>= 1) {
+            mine += __shfl_down(mine, d, 64);
+            const int o = __shfl_down(mx, d, 64);
+            mx = o > mx ? o : mx;
+        }
+        if ((tid & 63) == 0) { atomicAdd(&total, mine); atomicMax(&longest, mx); }
     }
     for (int i = tid; i < cap; i += 1024) out[i] = none;
     __syncthreads();
     const unsigned long long tot = total;
+    if (tid < SPLIT_MAX_PIECES) alike_cost[tid] = split_alike_cost(n_items, longest, tid + 1);
+    __syncthreads();
+    const SplitRule rule = split_rule(D, n_items, longest, tot, alike_cost);
     // partial-result slots in item order: thread t owns the items [lo, hi)
     const int per = (n_items + 1023) / 1024;
     const int lo = tid * per < n_items ? tid * per : n_items;
     const int hi = lo + per < n_items ? lo + per : n_items;
     int mine = 0;
     for (int i = lo; i < hi; ++i) {
-        const int P = split_pieces(count_of(i), tot, per_cu);
+        const int P = split_pieces(count_of(i), tot, rule);
         if (P > 1) mine += P;
     }
     const int first_slot = plan_block_scan(mine, wave_sum, tid);
     // pieces of item i: P (1 = whole) and the first partial slot
     auto pieces_of = [&](int c, int& run, int& P, int& slot0) {
-        const int want = split_pieces(c, tot, per_cu);
+        const int want = split_pieces(c, tot, rule);
         P = want;
         slot0 = -1;
         if (want > 1) {
@@ -358,14 +426,15 @@ constexpr int SMALL_BYTES = 1024 * SMALL_SWEEPS;
 
 __global__ __launch_bounds__(1024) void plan_small_kernel(
     const unsigned char* __restrict__ mask, const int32_t* __restrict__ kv_lens, int kv_len, int N, int block,
-    int H, int BH, int nb, int cap, int pmax, int per_cu,
+    int H, int BH, int nb, int cap, int pmax, int D,
     int32_t* __restrict__ counts, int32_t* __restrict__ index, PlanRec* __restrict__ recs,
     int32_t* __restrict__ arrived)
 {
     __shared__ unsigned rowbits[2 * SMALL_ITEMS]; // kept key-blocks of item i: bits of words 2i, 2i+1
     __shared__ int live[SMALL_ITEMS];            // per (b,h) pair: key-blocks that start below kv_len
     __shared__ int hist[128];                    // by r = nb - length; hist[nb + 1] = number of records
-    __shared__ int wave_sum[16], kept_sum[16];
+    __shared__ int wave_sum[16], kept_sum[16], wave_max[16];
+    __shared__ long long alike_cost[SPLIT_MAX_PIECES];
     const int x = blockIdx.x, tid = threadIdx.x;
     const int n_bh = BH > x ? (BH - x + XCDS - 1) / XCDS : 0;
     const int n_items = n_bh * nb;
@@ -455,9 +524,22 @@ __global__ __launch_bounds__(1024) void plan_small_kernel(
     const int item = has ? (int)(__umul24(div_nb(tid) * XCDS + x, nb) + (tid - __umul24(div_nb(tid), nb))) : 0;
     const int c = has ? __popc(rowbits[2 * tid]) + __popc(rowbits[2 * tid + 1]) : 0;
     if (has) counts[item] = c;
+    {                                             // the longest row, to every thread
+        const int mx = wave_max_to_last(c);
+        if ((tid & 63) == 63) wave_max[tid >> 6] = mx;
+    }
+    __syncthreads();
+    int longest = 0;
+#pragma unroll
+    for (int w = 0; w < 16; ++w) longest = wave_max[w] > longest ? wave_max[w] : longest;
+    if (D == 128 && rows_alike(n_items, longest, tot)) {   // the same for the whole workgroup
+        if (tid < SPLIT_MAX_PIECES) alike_cost[tid] = split_alike_cost(n_items, longest, tid + 1);
+        __syncthreads();
+    }
+    const SplitRule rule = split_rule(D, n_items, longest, tot, alike_cost);
     int want = 1;
     if (has && tot != 0u) {
-        unsigned P = (2u * (unsigned)c * (unsigned)(CUS_PER_XCD * per_cu) + tot) / (2u * tot);
+        unsigned P = rule.p_all ? (unsigned)rule.p_all : (2u * (unsigned)c * (unsigned)rule.g + tot) / (2u * tot);
         const unsigned by_len = (unsigned)c / SPLIT_MIN_BLOCKS;
         P = P > by_len ? by_len : P;
         P = P > (unsigned)SPLIT_MAX_PIECES ? SPLIT_MAX_PIECES : P;
@@ -1588,7 +1670,7 @@ int run_sparse(const Problem& pr, int block, const unsigned char* mask, void* wo
     const int xcd_items = plan_items(B, H, nb);
     if (block == 128 && nb <= SMALL_NB && xcd_items <= SMALL_ITEMS && xcd_items * nb <= SMALL_BYTES) {
         hipLaunchKernelGGL(plan_small_kernel, dim3(XCDS), dim3(1024), 0, s, mask, pr.kv_lens, pr.kv_len, N, block,
-                           H, B * H, nb, w.chunk, w.pmax, split_per_cu(D), counts, index, (PlanRec*)order,
+                           H, B * H, nb, w.chunk, w.pmax, D, counts, index, (PlanRec*)order,
                            (int32_t*)(ws + w.arrived_off));
     } else {
         hipLaunchKernelGGL(compact_mask_kernel, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, s,
@@ -1596,7 +1678,7 @@ int run_sparse(const Problem& pr, int block, const unsigned char* mask, void* wo
         if (hipGetLastError() != hipSuccess) return RAPID_ERR_DEVICE;
         if (block == 128)
             hipLaunchKernelGGL(plan_split_kernel, dim3(XCDS), dim3(1024), 0, s, counts, B * H, nb, w.chunk,
-                               w.pmax, split_per_cu(D), (PlanRec*)order, (int32_t*)(ws + w.arrived_off));
+                               w.pmax, D, (PlanRec*)order, (int32_t*)(ws + w.arrived_off));
         else
             hipLaunchKernelGGL(plan_kernel, dim3(XCDS), dim3(1024), 0, s, counts, B * H, nb, w.chunk, order);
     }

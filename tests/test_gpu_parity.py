@@ -140,14 +140,28 @@ def read_plan(ws, B, H, nb, D, block):
     return counts, order, index, g
 
 
-def split_pieces(c, total, D):
-    """Pieces of an item with c kept key-blocks when its XCD holds `total`: round(c / target) with
-    target = total / (32 CUs x 3) at D = 128 and total / (32 x 12) at D = 64, at most c // 8 (a
-    piece has at least 8 key-blocks) and 16."""
+def split_rule(counts_x, D):
+    """The rule of one XCD whose items keep counts_x blocks: (granules g, p_all).  P(c) =
+    round(c * g / total) pieces, or p_all for every item when that is not 0; at most c // 8 and 16.
+    D = 128: g = 32 x 3; rows all alike (8 n max <= 9 total): p_all = the first P in 1 .. max // 8
+    that minimises rounds(P) x (piece length + 2 + 2 [P > 1]) over the XCD's 64 places.
+    D = 64: g = 32 x 4, rows all alike: 32 x 12."""
+    n, total, longest = len(counts_x), int(np.sum(counts_x)), int(np.max(counts_x, initial=0))
+    alike = 8 * n * longest <= 9 * total
+    if D != 128:
+        return 32 * (12 if alike else 4), 0
+    p_all = 0
+    if alike and total:
+        cost = lambda P: -(-n * P // 64) * (-(-longest // P) + 2 + (2 if P > 1 else 0))
+        p_all = min(range(1, max(1, min(longest // 8, 16)) + 1), key=lambda P: (cost(P), P))
+    return 32 * 3, p_all
+
+
+def split_pieces(c, total, rule):
     if total == 0:
         return 1
-    g = 32 * (3 if D == 128 else 12)
-    return max(1, min((2 * c * g + total) // (2 * total), c // 8, 16))
+    g, p_all = rule
+    return max(1, min(p_all if p_all else (2 * c * g + total) // (2 * total), c // 8, 16))
 
 
 def check_plan(counts, order, g, B, H, nb, block, D=64):
@@ -171,10 +185,11 @@ def check_plan(counts, order, g, B, H, nb, block, D=64):
             continue
         assert (np.diff(ent[:, 2]) <= 0).all()
         total = int(counts[mine].sum())
+        rule = split_rule(counts[mine], D)
         want, run = [], 0
         for it in mine:
             c = int(counts[it])
-            P = split_pieces(c, total, D)
+            P = split_pieces(c, total, rule)
             slot0 = -1
             if P > 1:
                 if run + P <= g["pmax"]:
