@@ -183,6 +183,13 @@ def check_plan(counts, order, g, B, H, nb, block, D=64):
             assert sorted(ent[:, 0].tolist()) == mine
             assert (np.diff(counts[ent[:, 0]]) <= 0).all()
             continue
+        most = (B * H + 7) // 8 * nb                                    # items of the fullest XCD
+        if nb <= 64 and most <= 1024 and most * nb <= 8192:
+            # the one-launch planner: the odd rounds of 32 of the first wave (one record per place
+            # of the XCD: 32 CUs x 2 at D = 128, x 4 at D = 64) are stored backwards
+            ent = ent.copy()
+            for lo in range(32, min(n, 32 * (2 if D == 128 else 4)), 64):
+                ent[lo:lo + 32] = ent[lo:lo + 32][::-1].copy()
         assert (np.diff(ent[:, 2]) <= 0).all()
         total = int(counts[mine].sum())
         rule = split_rule(counts[mine], D)
