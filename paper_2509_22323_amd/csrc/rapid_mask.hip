@@ -155,7 +155,8 @@ __global__ __launch_bounds__(256) void select_blocks_kernel(const float* __restr
 // a strictly larger probability hold less than tau of the mass, a sum each lane forms for its
 // own blocks over all the others (nb^2 work per row, trivial at this size).
 constexpr int SMALL_NB = 256;
-constexpr int SMALL_ROWS = 16;
+constexpr int SMALL_RPW = 1;                   // mask rows per wavefront
+constexpr int SMALL_ROWS = 4 * SMALL_RPW;     // per workgroup
 
 template <int D>
 __global__ __launch_bounds__(256) void select_blocks_small_kernel(const float* __restrict__ qmean,
@@ -197,14 +198,16 @@ __global__ __launch_bounds__(256) void select_blocks_small_kernel(const float* _
         }
         if (j0 + 64 < live) fetch_chunk(j0 + 64);              // the next chunk travels during this one's work
         __syncthreads();
-        float dot[4] = {0.f, 0.f, 0.f, 0.f};
+        float dot[SMALL_RPW];
+#pragma unroll
+        for (int r = 0; r < SMALL_RPW; ++r) dot[r] = 0.f;
         const float* kr = kch + lane * KROW;
 #pragma unroll 4
         for (int d4 = 0; d4 < D / 4; ++d4) {
             const f32x4 kv = *(const f32x4*)(kr + 4 * d4);
 #pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const f32x4 qv = *(const f32x4*)(&qs[wv * 4 + r][4 * d4]);
+            for (int r = 0; r < SMALL_RPW; ++r) {
+                const f32x4 qv = *(const f32x4*)(&qs[wv * SMALL_RPW + r][4 * d4]);
                 dot[r] += qv[0] * kv[0];
                 dot[r] += qv[1] * kv[1];
                 dot[r] += qv[2] * kv[2];
@@ -213,13 +216,13 @@ __global__ __launch_bounds__(256) void select_blocks_small_kernel(const float* _
         }
         if (j0 + lane < live) {
 #pragma unroll
-            for (int r = 0; r < 4; ++r) ps[wv * 4 + r][j0 + lane] = scale * dot[r];
+            for (int r = 0; r < SMALL_RPW; ++r) ps[wv * SMALL_RPW + r][j0 + lane] = scale * dot[r];
         }
     }
     __builtin_amdgcn_wave_barrier();                           // a wavefront reads only the rows it wrote
 
-    for (int r = 0; r < 4; ++r) {
-        const int row = wv * 4 + r, i = i0 + row;
+    for (int r = 0; r < SMALL_RPW; ++r) {
+        const int row = wv * SMALL_RPW + r, i = i0 + row;
         if (i >= nb) break;
         unsigned char* out = mask + (bh * nb + i) * (size_t)nb;
         if (i >= live) {
