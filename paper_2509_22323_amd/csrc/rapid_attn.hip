@@ -910,6 +910,48 @@ __device__ __forceinline__ void write_output(const Rows& O, const f32x16 (&acc)[
     }
 }
 
+// The same output through LDS, for a wavefront whose 32 queries are the rows row0 .. row0 + 31.
+// A lane holds 8-byte pieces of ONE row, so storing from registers sends 32 short stretches of
+// 32 different rows with every instruction (16 instructions, 512 memory requests per
+// wavefront); written to `stage` first (row stride D*2 + 16 bytes: the 8-byte writes of the
+// 32 rows spread over the banks) and read back 16 bytes per lane along the rows, a store
+// instruction covers whole rows (8 or 4 instructions, a quarter of the requests).  `stage`
+// is this wavefront's own region of (D*2 + 16) * 32 bytes; nobody else may still be reading it.
+template <int D>
+__device__ __forceinline__ void write_output_rows(const Rows& O, const f32x16 (&acc)[D / 32], float l_part,
+                                                  int row0, bool qvalid, int N, int lane, char* stage)
+{
+    constexpr int RS = D * 2 + 16;
+    const int n = lane & 31, h = lane >> 5;
+    float l_run = l_part;
+    {
+        auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(l_run), __float_as_uint(l_run), false, false);
+        l_run = __uint_as_float(sw[0]) + __uint_as_float(sw[1]);
+    }
+    const float inv = (qvalid && l_run > 0.f) ? 1.0f / l_run : 0.f;
+#pragma unroll
+    for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            bf16x4 ov;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const float x = acc[db][4 * j + r] * inv;
+                ov[r] = (__bf16)((inv != 0.f) ? x : 0.f);
+            }
+            *(bf16x4*)(stage + n * RS + (32 * db + 8 * j + 4 * h) * 2) = ov;
+        }
+    constexpr int CH = D * 2 / 16;                // 16-byte chunks of a row
+    constexpr int RPI = 64 / CH;                  // rows per store instruction
+    const int rr = lane / CH, cc = lane % CH;
+#pragma unroll
+    for (int i = 0; i < 32 / RPI; ++i) {
+        const int r = i * RPI + rr;
+        const u32x4 v = *(const u32x4*)(stage + r * RS + cc * 16);
+        if (row0 + r < N) *(u32x4*)(const_cast<char*>(O.row(row0 + r)) + cc * 16) = v;
+    }
+}
+
 // Q^T fragments (B operand of S^T = K Q^T): lane (n, h) holds Q[qrow][16t + 8h .. +8].
 template <int D>
 __device__ __forceinline__ void load_q(const Rows& Q, int qrow, bool qvalid, int h, bf16x8 (&qf)[D / 16])
@@ -1493,8 +1535,16 @@ __global__ __launch_bounds__(256, (D == 64 ? 4 : 2)) void attn_sparse_sg_kernel(
         kn3 = (j + 4 < T) ? key_of(j + 4) : 0;
     }
 
+    // At D = 128 the output goes out row-wise through LDS (-1.5 % on a sparse call); at D = 64,
+    // with four workgroups on the CU and rows half as long, that was 2-3 % slower than direct.
+    char* out_stage = lds + wave * ((D * 2 + 16) * 32);
     if (rec.w < 0) {                              // the whole item
-        write_output<D>(O, acc, sm.l, qrow, qvalid, p.N, h);
+        if constexpr (D == 128) {
+            __syncthreads();                      // every wavefront has read its last tiles
+            write_output_rows<D>(O, acc, sm.l, qi * QT + wave * 32, qvalid, p.N, lane, out_stage);
+        } else {
+            write_output<D>(O, acc, sm.l, qrow, qvalid, p.N, h);
+        }
         return;
     }
 
@@ -1557,7 +1607,8 @@ __global__ __launch_bounds__(256, (D == 64 ? 4 : 2)) void attn_sparse_sg_kernel(
                 acc[db][2 * j + 1] += __uint_as_float((unsigned)(v >> 32)) * a;
             }
     }
-    write_output<D>(O, acc, l, qrow, qvalid, p.N, h);
+    if constexpr (D == 128) write_output_rows<D>(O, acc, l, qi * QT + wave * 32, qvalid, p.N, lane, out_stage);   // after the barriers above
+    else write_output<D>(O, acc, l, qrow, qvalid, p.N, h);
 }
 
 // ---------------------------------------------------------------------------
