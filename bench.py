@@ -142,6 +142,21 @@ def main():
         torch.cuda.synchronize()
         return a.elapsed_time(b) / (replays * calls)
 
+    def time_region(fn, steps, warmup):
+        """The timed region proper: `steps` calls back to back, nothing else in the stream; wall ms
+        per step between synchronisations and HIP-event ms per step over the same region."""
+        for _ in range(warmup):
+            fn()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        a.record()
+        for _ in range(steps):
+            fn()
+        b.record()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / steps, a.elapsed_time(b) / steps
+
     # ---- the timed K steps: dense entry point
     dense_call = lambda: ra.rapid_attn_dense(dq, dk, dv, do, w.kv_len)
     t_ramp = time.perf_counter()
@@ -149,9 +164,12 @@ def main():
         for _ in range(20):
             dense_call()
         torch.cuda.synchronize()
-    wall_ms, ev_mean, ev_min = time_calls(dense_call, args.steps, args.warmup)
+    wall_ms, ev_mean = time_region(dense_call, args.steps, args.warmup)
     value = dense_flops / (wall_ms * 1e-3) / 1e12
     achieved = dense_flops / (ev_mean * 1e-3) / 1e12
+    # one launch at a time between its own pair of events (the events themselves open a gap of a
+    # few microseconds between launches, which is why the timed region above has none inside)
+    _, _, ev_min = time_calls(dense_call, min(args.steps, 200), 0)
 
     out = {
         "metric": "effective TFLOP/s (4*B*H*N^2*D*density), dense joint attention",
@@ -209,7 +227,7 @@ def main():
             mask = w.mask(d)
             eff = wl.effective_density(mask, w.block, w.kv_len)
             dm = torch.from_numpy(mask).cuda()
-            s_wall, s_mean, s_min = time_calls(
+            _, s_mean = time_region(
                 lambda: ra.rapid_attn_block_sparse(dq, dk, dv, do, dm, w.block, w.kv_len, 0.0, ws),
                 max(20, min(200, args.steps // 2)), max(5, args.warmup // 2))
             sparse.append({"density_nominal": d, "density_effective": round(eff, 4),
@@ -229,8 +247,8 @@ def main():
                 fused[:, :, j] = x[:, :, a:b].permute(0, 2, 1, 3)
             o_seg = torch.empty(w.B, b - a, w.H, w.D, dtype=torch.bfloat16, device="cuda")
             segs.append(tuple(fused[:, :, j].permute(0, 2, 1, 3) for j in range(3)) + (o_seg.permute(0, 2, 1, 3),))
-        _, j_mean, j_min = time_calls(lambda: ra.rapid_attn_joint(segs, None, w.block, kv_len=w.kv_len),
-                                      max(20, min(200, args.steps // 2)), max(5, args.warmup // 2))
+        _, j_mean = time_region(lambda: ra.rapid_attn_joint(segs, None, w.block, kv_len=w.kv_len),
+                                max(20, min(200, args.steps // 2)), max(5, args.warmup // 2))
         out["joint_layout"] = {"layout": f"{len(segs)} segment(s), fused [B,n,3,H,D] inputs, [B,n,H,D] outputs",
                                "ms": round(j_mean, 5), "tflops": round(dense_flops / (j_mean * 1e-3) / 1e12, 2),
                                "time_over_contiguous": round(j_mean / ev_mean, 3)}
