@@ -1177,7 +1177,15 @@ __device__ __forceinline__ void dense_item(const AttnParams& p, char* lds, int b
     }
     if (group == 0) __syncthreads();              // same number of barriers for every wavefront
 
-    write_output<D>(O, acc, sm.l, qrow, qvalid, p.N, h);
+    if constexpr (D == 128) {
+        // row-wise through LDS (see write_output_rows); group 0 waits here until group 1 is
+        // through its last matrix phase and the stages are free, which costs nothing: the
+        // workgroup ends, and its CU takes the next one, when group 1 is done either way
+        __syncthreads();
+        write_output_rows<D>(O, acc, sm.l, q0 + wave * 32, qvalid, p.N, lane, lds + wave * ((D * 2 + 16) * 32));
+    } else {
+        write_output<D>(O, acc, sm.l, qrow, qvalid, p.N, h);
+    }
 }
 
 // (D = 64: 64 KB of LDS and <= 128 VGPRs, so two workgroups share a CU: four wavefronts per
