@@ -102,9 +102,9 @@ RAPID_API int rapid_attn_dense(const void* q, const void* k, const void* v, void
  *                          with c kept blocks, in an XCD whose items keep
  *                          `total` blocks, is cut into
  *                          P = max(1, min(round(c*g/total), c/8, 16))
- *                          pieces [c*k/P, c*(k+1)/P), g = 32 CUs x 3 at
+ *                          pieces [c*k/P, c*(k+1)/P), g = 32 CUs x 2.5 at
  *                          D = 128 and 32 x 4 at D = 64 (pieces of about
- *                          a third / a quarter of a CU's share, at least
+ *                          0.4 / a quarter of a CU's share, at least
  *                          8 key-blocks each), whose partial results are
  *                          added up in piece order.  When the XCD's n rows
  *                          are all alike (8 n max(c) <= 9 total): g =

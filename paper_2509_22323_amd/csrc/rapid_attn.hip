@@ -252,7 +252,7 @@ constexpr int ENTRY_COST = 2, PIECE_COST = 2;    // measured, in key-blocks of t
 // The rule of one XCD.  P(c) = round(c * g / total) pieces for an item with c kept key-blocks
 // (g granules: pieces of about total / g), or p_all pieces for every item when that is set;
 // in both cases at most c / SPLIT_MIN_BLOCKS and SPLIT_MAX_PIECES, at least 1.
-//   D = 128: g = 32 CUs x 3.  Rows that are all about alike (the longest within 1/9 of the
+//   D = 128: g = 32 CUs x 2.5.  Rows that are all about alike (the longest within 1/9 of the
 //     mean: an all-ones mask) are not told apart by their lengths; what matters then is how
 //     many rounds the 64 places of the XCD need, so p_all is the P that minimises
 //     rounds(P) * (piece length + cost of an entry), the first such P.
@@ -283,7 +283,7 @@ __device__ __forceinline__ SplitRule split_rule(int D, int n_items, int max_c, u
     r.p_all = 0;
     const bool alike = rows_alike(n_items, max_c, total);
     if (D == 128) {
-        r.g = CUS_PER_XCD * 3;
+        r.g = CUS_PER_XCD * 5 / 2;
         if (alike && total != 0ull) {
             long long best = costs[0];
             r.p_all = 1;

@@ -143,7 +143,7 @@ def read_plan(ws, B, H, nb, D, block):
 def split_rule(counts_x, D):
     """The rule of one XCD whose items keep counts_x blocks: (granules g, p_all).  P(c) =
     round(c * g / total) pieces, or p_all for every item when that is not 0; at most c // 8 and 16.
-    D = 128: g = 32 x 3; rows all alike (8 n max <= 9 total): p_all = the first P in 1 .. max // 8
+    D = 128: g = 32 x 2.5; rows all alike (8 n max <= 9 total): p_all = the first P in 1 .. max // 8
     that minimises rounds(P) x (piece length + 2 + 2 [P > 1]) over the XCD's 64 places.
     D = 64: g = 32 x 4, rows all alike: 32 x 12."""
     n, total, longest = len(counts_x), int(np.sum(counts_x)), int(np.max(counts_x, initial=0))
@@ -154,7 +154,7 @@ def split_rule(counts_x, D):
     if alike and total:
         cost = lambda P: -(-n * P // 64) * (-(-longest // P) + 2 + (2 if P > 1 else 0))
         p_all = min(range(1, max(1, min(longest // 8, 16)) + 1), key=lambda P: (cost(P), P))
-    return 32 * 3, p_all
+    return 80, p_all
 
 
 def split_pieces(c, total, rule):
