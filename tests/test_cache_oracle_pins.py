@@ -128,6 +128,33 @@ def test_equivalent_steps_worked_examples():
     assert co.C_SPARSE == (0.0, 0.05, 0.07, 0.10) and co.C_CACHE == 0.95 and co.LAMBDA == 0.97 and co.OMEGA == 1.0
 
 
+def paper_reward_constants():
+    """tests/golden/reward_constants.txt: the values the paper prints (its citation is in the file)."""
+    import os
+    vals = {}
+    with open(os.path.join(os.path.dirname(__file__), "golden", "reward_constants.txt")) as f:
+        for line in f:
+            if line.strip() and not line.startswith("#"):
+                name, *rest = line.split()
+                vals[name] = [float(x) for x in rest]
+    return vals
+
+
+def test_constants_are_the_ones_the_paper_prints():
+    g = paper_reward_constants()
+    assert [co.LAMBDA] == g["lambda"] and [co.OMEGA] == g["omega"] and [co.C_CACHE] == g["C_cache"]
+    assert list(co.C_SPARSE) == [0.0] + g["C_sparse"]         # action 0 is dense: no reduction
+    # the product side: defaults of the reward entry point's binding
+    import inspect
+    import paper_2509_22323_amd.binding as binding
+    sig = inspect.signature(binding.rapid_reward)
+    assert [sig.parameters["lam"].default] == g["lambda"] and [sig.parameters["omega"].default] == g["omega"]
+    # a step that reuses the cache costs 1 - C_cache; with the printed values 28 plain steps weigh
+    # as much as 560 cached ones
+    k, _ = co.equivalent_steps(*co.step_costs([1] * 560, [0] * 560))
+    assert abs(k - 28.0) < 1e-9
+
+
 def test_reward_is_the_geometric_series():
     q, d = 0.8, 0.3
     for K in (1, 2, 8, 16, 28):
