@@ -129,6 +129,30 @@ RAPID_API int rapid_attn_block_sparse(const void* q, const void* k, const void* 
                             const unsigned char* mask, int kv_len, float scale,
                             void* workspace, size_t workspace_bytes, void* stream);
 
+/*
+ * rapid_attn_block_sparse without a workspace argument, for callers that cannot
+ * allocate device memory: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  Same arguments, semantics and kernels as
+ * rapid_attn_block_sparse; the scratch is a fixed array of
+ * RAPID_ATTN_STATIC_SCRATCH_BYTES inside the library's code object (one copy per
+ * GPU, held until the process ends), and the call allocates and frees nothing.
+ *   - A shape whose counts, lists and plan alone exceed the array returns
+ *     RAPID_ERR_WORKSPACE.  When only the partial-result slots of split items do
+ *     not all fit, fewer slots are used (fewer long rows are cut into pieces;
+ *     results stay within the stated tolerances, and are bit-identical to
+ *     rapid_attn_block_sparse whenever everything fits, e.g. B*H <= 24 at
+ *     N <= 4608).
+ *   - All calls on one GPU share that GPU's array: two calls that can run
+ *     concurrently on one GPU (different streams, or different host threads on
+ *     streams that are not ordered) race.  Calls on one stream are ordered.
+ *   - The first call on a device looks the array's address up
+ *     (hipGetSymbolAddress); make that call outside graph capture.
+ */
+#define RAPID_ATTN_STATIC_SCRATCH_BYTES (64u << 20)
+RAPID_API int rapid_attn_block_sparse_static(const void* q, const void* k, const void* v, void* o,
+                            int B, int H, int N, int D, int block,
+                            const unsigned char* mask, int kv_len, float scale, void* stream);
+
 /* Bytes of workspace rapid_attn_block_sparse needs for this shape; 0 if the
  * shape is invalid or unsupported.  Pure host arithmetic. */
 RAPID_API size_t rapid_attn_workspace_bytes(int B, int H, int N, int D, int block);

@@ -18,7 +18,8 @@ STATUS = {
     "RAPID_ERR_ALIGN": -4, "RAPID_ERR_WORKSPACE": -5, "RAPID_ERR_DEVICE": -6,
 }
 
-EXPORTS = ("rapid_attn_dense", "rapid_attn_block_sparse", "rapid_attn_workspace_bytes",
+EXPORTS = ("rapid_attn_dense", "rapid_attn_block_sparse", "rapid_attn_block_sparse_static",
+           "rapid_attn_workspace_bytes",
            "rapid_attn_joint", "rapid_attn_joint_workspace_bytes",
            "rapid_attn_status_string", "rapid_attn_version")
 
@@ -70,6 +71,8 @@ def library():
     lib.rapid_attn_dense.restype = ci
     lib.rapid_attn_block_sparse.argtypes = [vp, vp, vp, vp, ci, ci, ci, ci, ci, vp, ci, cf, vp, sz, vp]
     lib.rapid_attn_block_sparse.restype = ci
+    lib.rapid_attn_block_sparse_static.argtypes = [vp, vp, vp, vp, ci, ci, ci, ci, ci, vp, ci, cf, vp]
+    lib.rapid_attn_block_sparse_static.restype = ci
     lib.rapid_attn_workspace_bytes.argtypes = [ci, ci, ci, ci, ci]
     lib.rapid_attn_workspace_bytes.restype = sz
     lib.rapid_attn_joint.argtypes = [ctypes.POINTER(Segment), ci, ci, ci, ci, ci, vp, ci, vp, cf, vp, sz, vp]
@@ -163,6 +166,26 @@ def rapid_attn_block_sparse(q, k, v, o, mask, block, kv_len=None, scale=0.0, wor
     _check(library().rapid_attn_block_sparse(
         q.data_ptr(), k.data_ptr(), v.data_ptr(), o.data_ptr(), B, H, N, D, int(block),
         mask.data_ptr(), kv_len, float(scale), workspace.data_ptr(), ws_bytes, _stream(q)))
+    return o
+
+
+STATIC_SCRATCH_BYTES = 64 << 20
+
+
+def rapid_attn_block_sparse_static(q, k, v, o, mask, block, kv_len=None, scale=0.0):
+    """rapid_attn_block_sparse on the library's own fixed scratch array: neither this wrapper nor
+    the call allocates device memory.  All calls on one GPU share the array."""
+    import torch
+    B, H, N, D = _qkvo(q, k, v, o)
+    kv_len = N if kv_len is None else int(kv_len)
+    if not (isinstance(mask, torch.Tensor) and mask.is_cuda and mask.dtype == torch.uint8
+            and mask.is_contiguous() and mask.device == q.device):
+        raise TypeError("mask must be a contiguous CUDA uint8 tensor")
+    if block > 0 and N % block == 0 and tuple(mask.shape) != (B, H, N // block, N // block):
+        raise ValueError(f"mask shape {tuple(mask.shape)} != {(B, H, N // block, N // block)}")
+    _check(library().rapid_attn_block_sparse_static(
+        q.data_ptr(), k.data_ptr(), v.data_ptr(), o.data_ptr(), B, H, N, D, int(block),
+        mask.data_ptr(), kv_len, float(scale), _stream(q)))
     return o
 
 

@@ -31,7 +31,12 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
+
 #include "rapid_attn.h"
+
+// Scratch of the entry point that allocates nothing (see static_scratch below).
+static __device__ __align__(256) unsigned char scratch[RAPID_ATTN_STATIC_SCRATCH_BYTES];
 
 namespace {
 
@@ -1635,7 +1640,9 @@ inline int plan_items(int B, int H, int nb) { return ((B * H + XCDS - 1) / XCDS)
 
 // 64-token tiles:  counts | order int32[8*chunk]   | index
 // 128-token tiles: counts | records PlanRec[8*chunk] | index | arrived int32[8*pmax] | partial slots [8*pmax]
-inline WorkspaceLayout workspace_layout(int B, int H, int nb, int D, int block)
+// `slots` < 0: as many partial-result slots per XCD as the split rule can ever use
+// (min(256, items)); otherwise that many at most (fewer slots = fewer items cut).
+inline WorkspaceLayout workspace_layout(int B, int H, int nb, int D, int block, int slots = -1)
 {
     const size_t rows = (size_t)B * H * nb;
     auto up = [](size_t x) { return (x + 255) & ~(size_t)255; };
@@ -1645,6 +1652,7 @@ inline WorkspaceLayout workspace_layout(int B, int H, int nb, int D, int block)
     w.order_off = up(rows * 4);
     if (block == 128) {
         w.pmax = SPLIT_SLOTS < items ? SPLIT_SLOTS : items;
+        if (slots >= 0 && slots < w.pmax) w.pmax = slots;
         w.chunk = items + w.pmax;
         w.index_off = w.order_off + up((size_t)XCDS * w.chunk * sizeof(PlanRec));
         w.arrived_off = w.index_off + up(rows * (size_t)nb * 4);
@@ -1721,13 +1729,13 @@ int run_dense(const Problem& pr, void* stream)
 
 // nb = ceil(N / block): the last mask block may be ragged (it then ends at N)
 int run_sparse(const Problem& pr, int block, const unsigned char* mask, void* workspace, size_t workspace_bytes,
-               void* stream)
+               void* stream, int slots = -1)
 {
     const int B = pr.B, H = pr.H, N = pr.N, D = pr.D;
     const int nb = (N + block - 1) / block;
     const long long rows = (long long)B * H * nb;
     if (rows > 0x7fffffffLL / 16) return RAPID_ERR_SHAPE;
-    const WorkspaceLayout w = workspace_layout(B, H, nb, D, block);
+    const WorkspaceLayout w = workspace_layout(B, H, nb, D, block, slots);
     if (!workspace || workspace_bytes < w.total) return RAPID_ERR_WORKSPACE;
     if (!aligned16(workspace)) return RAPID_ERR_ALIGN;
 
@@ -1785,6 +1793,26 @@ Problem contiguous_problem(const void* q, const void* k, const void* v, void* o,
     pr.kv_len = kv_len; pr.kv_lens = nullptr;
     pr.scale = scale > 0.f ? scale : 1.0f / sqrtf((float)D);
     return pr;
+}
+
+// The scratch of rapid_attn_block_sparse_static: one array per GPU, part of the loaded code
+// object, alive until the process ends.  In host code `scratch` is only a handle for
+// hipGetSymbolAddress; the device address is looked up once per device, with that device
+// current, and kept.
+constexpr int MAX_DEVICES = 64;
+std::atomic<void*> scratch_ptr[MAX_DEVICES];
+
+int static_scratch(void** out)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) return RAPID_ERR_DEVICE;
+    void* ptr = scratch_ptr[dev].load(std::memory_order_acquire);
+    if (ptr == nullptr) {
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || ptr == nullptr) return RAPID_ERR_DEVICE;
+        scratch_ptr[dev].store(ptr, std::memory_order_release);   // two threads racing store the same address
+    }
+    *out = ptr;
+    return RAPID_OK;
 }
 
 }  // namespace
@@ -1873,6 +1901,33 @@ int rapid_attn_joint(const rapid_attn_segment* segments, int n_segments, int B, 
     pr.scale = scale > 0.f ? scale : 1.0f / sqrtf((float)D);
     if (!mask) return run_dense(pr, stream);
     return run_sparse(pr, block, mask, workspace, workspace_bytes, stream);
+}
+
+int rapid_attn_block_sparse_static(const void* q, const void* k, const void* v, void* o,
+                                   int B, int H, int N, int D, int block,
+                                   const unsigned char* mask, int kv_len, float scale, void* stream)
+{
+    if (!mask) return RAPID_ERR_NULL;
+    const int rc = check_common(q, k, v, o, B, H, N, D, kv_len);
+    if (rc != RAPID_OK) return rc;
+    if (block != 64 && block != 128) return RAPID_ERR_UNSUPPORTED;
+    if (N % block != 0) return RAPID_ERR_SHAPE;
+    const int nb = N / block;
+    if ((long long)B * H * nb > 0x7fffffffLL / 16) return RAPID_ERR_SHAPE;
+    // as many partial-result slots as fit next to the lists (fewer slots: fewer items are cut)
+    const WorkspaceLayout none = workspace_layout(B, H, nb, D, block, 0);
+    if (none.total > (size_t)RAPID_ATTN_STATIC_SCRATCH_BYTES) return RAPID_ERR_WORKSPACE;
+    int slots = -1;
+    if (workspace_layout(B, H, nb, D, block).total > (size_t)RAPID_ATTN_STATIC_SCRATCH_BYTES) {
+        const size_t per_slot = XCDS * ((D == 64 ? PartialSlot<64>::BYTES : PartialSlot<128>::BYTES) + sizeof(PlanRec) + 4);
+        slots = (int)(((size_t)RAPID_ATTN_STATIC_SCRATCH_BYTES - none.total) / per_slot);
+        while (slots > 0 && workspace_layout(B, H, nb, D, block, slots).total > (size_t)RAPID_ATTN_STATIC_SCRATCH_BYTES) --slots;
+    }
+    void* ws = nullptr;
+    const int rs = static_scratch(&ws);
+    if (rs != RAPID_OK) return rs;
+    return run_sparse(contiguous_problem(q, k, v, o, B, H, N, D, kv_len, scale), block, mask, ws,
+                      (size_t)RAPID_ATTN_STATIC_SCRATCH_BYTES, stream, slots);
 }
 
 size_t rapid_attn_joint_workspace_bytes(int B, int H, int N, int D, int block)
