@@ -28,7 +28,7 @@
  * Memory: every pointer except `stream` is a DEVICE pointer owned by the
  * caller.  Q, K, V, O are bf16 [B, H, N, D] contiguous, D fastest.  Q/K/V/mask
  * are read-only; O is fully overwritten ([B,H,N,D], padded rows included) and
- * must not alias an input.  The library allocates nothing, keeps no state
+ * must not overlap an input (checked for the contiguous entry points).  The library allocates nothing, keeps no state
  * between calls and never synchronises: kernels are enqueued on `stream`
  * (a hipStream_t; NULL = the default stream) and the call returns at once.
  *
@@ -52,17 +52,19 @@ extern "C" {
 typedef enum {
     RAPID_OK              =  0,
     RAPID_ERR_NULL        = -1,  /* a required pointer is NULL                        */
-    RAPID_ERR_SHAPE       = -2,  /* B,H,N <= 0; kv_len outside 1..N; N % block != 0   */
+    RAPID_ERR_SHAPE       = -2,  /* B,H,N <= 0; kv_len outside 1..N; N % block != 0;
+                                    N > 2^22; B*H > 524287                            */
     RAPID_ERR_UNSUPPORTED = -3,  /* D not in {64,128}; block not in {64,128}          */
     RAPID_ERR_ALIGN       = -4,  /* q/k/v/o/workspace not 16-byte aligned             */
     RAPID_ERR_WORKSPACE   = -5,  /* workspace NULL or smaller than required           */
-    RAPID_ERR_DEVICE      = -6   /* the HIP runtime refused a launch                  */
+    RAPID_ERR_DEVICE      = -6,  /* the HIP runtime refused a launch                  */
+    RAPID_ERR_ALIAS       = -7   /* o shares bytes with q, k or v (contiguous entries) */
 } rapid_status;
 
 /*
  * Dense joint attention (Sec. 3.1 Eq. 1; action 0 of Sec. 3.3 (c)).
  *   q,k,v   device, bf16 [B,H,N,D]           o   device, bf16 [B,H,N,D]
- *   N       tokens as allocated (any positive count)
+ *   N       tokens as allocated, 1 .. 2^22; B*H <= 524287
  *   D       head dimension, 64 or 128
  *   kv_len  valid tokens, 1..N, a prefix of the sequence: keys >= kv_len are
  *           ignored, query rows >= kv_len produce 0
@@ -82,46 +84,40 @@ RAPID_API int rapid_attn_dense(const void* q, const void* k, const void* v, void
  *           key-block); nonzero = keep the tile.  One mask per (sample, head),
  *           as the sparsity control is per layer and per head.
  *   workspace  device scratch of at least rapid_attn_workspace_bytes(...)
- *           bytes, 16-byte aligned.  The call first compacts the mask into
- *           it, then runs attention over the kept tiles only.  With
- *           nb = N/block, items = ceil(B*H/8)*nb, and each array starting at
- *           the next 256-byte boundary after the previous one:
+ *           bytes, 16-byte aligned.  Its contents on entry do not matter and
+ *           nothing in it survives as state: every call first compacts the
+ *           mask into it (kept key-blocks per query-block, blocks starting at
+ *           or beyond kv_len dropped), lays out its launch plan there, and
+ *           then runs attention over the kept tiles only; rows that keep many
+ *           tiles may be cut into pieces whose partial results pass through it.
+ *           One workspace must not serve two calls that can run concurrently
+ *           (different streams): each call rewrites all of it.  Calls on one
+ *           stream, and replays of a captured graph, may share it.
+ *           What it holds after a call (for tests and tools; may change with
+ *           RAPID_ATTN_VERSION).  nb = N/block, items = ceil(B*H/8)*nb, each
+ *           array starting at the next 256-byte boundary after the previous:
  *             int32 counts [B*H*nb]      kept key-blocks of each query-block
- *                                        (blocks starting at or beyond kv_len
- *                                        are dropped)
- *             launch plan, 8 segments of `chunk` entries: segment x holds the
+ *             launch plan, 8 segments of `chunk` entries; segment x holds the
  *                                        work of the (b,h) pairs with
- *                                        (b*H+h) % 8 == x, longest entry
- *                                        first, then entries meaning "none"
+ *                                        (b*H+h) % 8 == x, then "none" entries
  *               block 64:  chunk = items; entry = int32 item id
  *                          b*H*nb + h*nb + i, none = -1
- *               block 128: chunk = items + pmax; entry = 4 x int32
- *                          (item, first, n, w): n kept key-blocks of the item
- *                          starting at position `first` of its list; none =
- *                          (-1,0,0,-1).  w = -1 for a whole item.  An item
- *                          with c kept blocks, in an XCD whose items keep
- *                          `total` blocks, is cut into
- *                          P = max(1, min(round(c*g/total), c/8, 16))
- *                          pieces [c*k/P, c*(k+1)/P), g = 32 CUs x 2.5 at
- *                          D = 128 and 32 x 4 at D = 64 (pieces of about
- *                          0.4 / a quarter of a CU's share, at least
- *                          8 key-blocks each), whose partial results are
- *                          added up in piece order.  When the XCD's n rows
- *                          are all alike (8 n max(c) <= 9 total): g =
- *                          32 x 12 at D = 64; at D = 128 every item takes
- *                          the first P in 1 .. max(c)/8 that minimises
- *                          ceil(n P / 64) (ceil(max(c) / P) + 2 + 2 [P>1]);
- *                          w = (slot << 8) | (k << 4) | (P-1), the slots
- *                          (pmax = min(256, items) per XCD) handed out in
- *                          item order; an item that no longer fits stays
- *                          whole.
+ *               block 128: chunk = items + pmax, pmax = min(256, items);
+ *                          entry = 4 x int32 (item, first, n, w): n kept
+ *                          key-blocks of the item starting at position `first`
+ *                          of its list; none = (-1,0,0,-1); w = -1 for a whole
+ *                          item, else (slot << 8) | (k << 4) | (P-1) for piece
+ *                          k of P, slot = first of the item's P partial-result
+ *                          slots.  The pieces of an item cover its list once,
+ *                          in order of k.
  *             int32 index  [B*H*nb*nb]   ascending kept key-blocks, row-wise;
  *                                        entries past counts[] are undefined
- *             block 128 only: int32 arrived [8*pmax] and the partial-result
- *                                        slots [8*pmax] of 64 KB + 2 KB
- *                                        (D=128) or 32 KB + 2 KB (D=64)
- *           Contents are outputs of the call; the layout is stated so tests
- *           can check the compaction and the plan bit for bit.
+ *             block 128 only: int32 arrived [8*pmax] (pieces of a cut item
+ *                                        that have finished, at its first
+ *                                        slot) and the partial-result slots
+ *   N       as rapid_attn_dense, and a multiple of block
+ *   limits  N <= 2^22 and B*H <= 524287 (RAPID_ERR_SHAPE beyond), for the
+ *           dense call too
  *   other arguments as rapid_attn_dense.
  */
 RAPID_API int rapid_attn_block_sparse(const void* q, const void* k, const void* v, void* o,

@@ -15,7 +15,7 @@ _lib = None
 
 STATUS = {
     "RAPID_OK": 0, "RAPID_ERR_NULL": -1, "RAPID_ERR_SHAPE": -2, "RAPID_ERR_UNSUPPORTED": -3,
-    "RAPID_ERR_ALIGN": -4, "RAPID_ERR_WORKSPACE": -5, "RAPID_ERR_DEVICE": -6,
+    "RAPID_ERR_ALIGN": -4, "RAPID_ERR_WORKSPACE": -5, "RAPID_ERR_DEVICE": -6, "RAPID_ERR_ALIAS": -7,
 }
 
 EXPORTS = ("rapid_attn_dense", "rapid_attn_block_sparse", "rapid_attn_block_sparse_static",

@@ -32,6 +32,7 @@
 #include <stdint.h>
 
 #include <atomic>
+#include <initializer_list>
 
 #include "rapid_attn.h"
 
@@ -1678,6 +1679,12 @@ int check_common(const void* q, const void* k, const void* v, const void* o,
     if (N > (1 << 22)) return RAPID_ERR_SHAPE;
     if (D != 64 && D != 128) return RAPID_ERR_UNSUPPORTED;
     if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o)) return RAPID_ERR_ALIGN;
+    // O is written while other workgroups still read Q, K and V: it must not share a byte with them
+    const uintptr_t bytes = (uintptr_t)B * H * N * D * 2, ob = (uintptr_t)o;
+    for (const void* in : {q, k, v}) {
+        const uintptr_t ib = (uintptr_t)in;
+        if (ob < ib + bytes && ib < ob + bytes) return RAPID_ERR_ALIAS;
+    }
     return RAPID_OK;
 }
 
@@ -1960,6 +1967,7 @@ const char* rapid_attn_status_string(int status)
         case RAPID_ERR_ALIGN: return "q/k/v/o/workspace must be 16-byte aligned";
         case RAPID_ERR_WORKSPACE: return "workspace is NULL or smaller than rapid_attn_workspace_bytes()";
         case RAPID_ERR_DEVICE: return "HIP runtime refused the launch";
+        case RAPID_ERR_ALIAS: return "o overlaps q, k or v";
         default: return "unknown status";
     }
 }

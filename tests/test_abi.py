@@ -93,6 +93,40 @@ def test_sparse_argument_errors(kw, code):
     assert sparse(**kw) == S[code]
 
 
+def test_output_must_not_overlap_an_input():
+    size = 1 * 2 * 256 * 64 * 2
+    assert dense(o=A) == S["RAPID_ERR_ALIAS"]                          # o is q
+    assert dense(o=A + 0x100000 + size - 16) == S["RAPID_ERR_ALIAS"]    # o starts in k's last row
+    assert dense(o=A + 0x200000 - size + 16) == S["RAPID_ERR_ALIAS"]    # o ends in v's first row
+    assert sparse(o=A + 0x200000) == S["RAPID_ERR_ALIAS"]
+    assert dense(o=A + 0x100000 + size, kv_len=0) == S["RAPID_ERR_SHAPE"]   # adjacent is fine (fails later, on kv_len)
+
+
+def test_documented_size_limits():
+    assert dense(N=(1 << 22) + 64, kv_len=64) == S["RAPID_ERR_SHAPE"]
+    assert dense(B=1024, H=512) == S["RAPID_ERR_SHAPE"]                 # B*H = 524288
+    assert re.search(r"2\^22", HEADER) and "524287" in HEADER
+
+
+def static(q=A, k=A + 0x100000, v=A + 0x200000, o=A + 0x300000, B=1, H=2, N=256, D=64, block=64,
+           mask=A + 0x400000, kv_len=256):
+    return ra.library().rapid_attn_block_sparse_static(q, k, v, o, B, H, N, D, block, mask, kv_len, 0.0, None)
+
+
+@pytest.mark.parametrize("kw,code", [
+    (dict(mask=None), "RAPID_ERR_NULL"), (dict(q=None), "RAPID_ERR_NULL"),
+    (dict(H=0), "RAPID_ERR_SHAPE"), (dict(N=320, kv_len=300, block=128), "RAPID_ERR_SHAPE"),
+    (dict(block=96), "RAPID_ERR_UNSUPPORTED"), (dict(D=32), "RAPID_ERR_UNSUPPORTED"),
+    (dict(v=A + 0x200008), "RAPID_ERR_ALIGN"), (dict(o=A), "RAPID_ERR_ALIAS"),
+    # the kept-block lists alone (B*H*nb*nb*4 bytes = 512 MiB) exceed the fixed array
+    (dict(B=64, H=32, N=16384, kv_len=16384, q=1 << 40, k=2 << 40, v=3 << 40, o=4 << 40), "RAPID_ERR_WORKSPACE"),
+])
+def test_static_scratch_entry_argument_errors(kw, code):
+    assert static(**kw) == S[code]
+    limit = int(re.search(r"#define RAPID_ATTN_STATIC_SCRATCH_BYTES \((\d+)u << (\d+)\)", HEADER).group(1)) << 20
+    assert limit == ra.STATIC_SCRATCH_BYTES
+
+
 def test_binding_rejects_non_tensors_and_raises_on_status():
     with pytest.raises(TypeError):
         ra.rapid_attn_dense(1, 2, 3, 4)

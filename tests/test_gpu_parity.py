@@ -115,7 +115,7 @@ def test_custom_scale_and_peaky_inputs():
 
 
 def plan_geometry(B, H, nb, D, block):
-    """Workspace geometry of the sparse entry point, as its header states it."""
+    """Where the arrays of the sparse entry point's workspace lie, as its header states it."""
     up = lambda x: (x + 255) // 256 * 256
     rows = B * H * nb
     items = (B * H + 7) // 8 * nb
@@ -127,7 +127,9 @@ def plan_geometry(B, H, nb, D, block):
         pmax, chunk, rec_bytes = 0, items, 4
     off_order = up(rows * 4)
     off_index = off_order + up(8 * chunk * rec_bytes)
-    return dict(rows=rows, pmax=pmax, chunk=chunk, off_order=off_order, off_index=off_index)
+    off_arrived = off_index + up(rows * nb * 4)
+    return dict(rows=rows, pmax=pmax, chunk=chunk, off_order=off_order, off_index=off_index,
+                off_arrived=off_arrived)
 
 
 def read_plan(ws, B, H, nb, D, block):
@@ -137,80 +139,67 @@ def read_plan(ws, B, H, nb, D, block):
     width = 4 if block == 128 else 1
     order = ws[g["off_order"]:g["off_order"] + 8 * chunk * 4 * width].view(np.int32).reshape(8, chunk, width)
     index = ws[g["off_index"]:g["off_index"] + rows * nb * 4].view(np.int32).reshape(rows, nb)
+    g["arrived"] = ws[g["off_arrived"]:g["off_arrived"] + 8 * g["pmax"] * 4].view(np.int32)
     return counts, order, index, g
 
 
-def split_rule(counts_x, D):
-    """The rule of one XCD whose items keep counts_x blocks: (granules g, p_all).  P(c) =
-    round(c * g / total) pieces, or p_all for every item when that is not 0; at most c // 8 and 16.
-    D = 128: g = 32 x 2.5; rows all alike (8 n max <= 9 total): p_all = the first P in 1 .. max // 8
-    that minimises rounds(P) x (piece length + 2 + 2 [P > 1]) over the XCD's 64 places.
-    D = 64: g = 32 x 4, rows all alike: 32 x 12."""
-    n, total, longest = len(counts_x), int(np.sum(counts_x)), int(np.max(counts_x, initial=0))
-    alike = 8 * n * longest <= 9 * total
-    if D != 128:
-        return 32 * (12 if alike else 4), 0
-    p_all = 0
-    if alike and total:
-        cost = lambda P: -(-n * P // 64) * (-(-longest // P) + 2 + (2 if P > 1 else 0))
-        p_all = min(range(1, max(1, min(longest // 8, 16)) + 1), key=lambda P: (cost(P), P))
-    return 80, p_all
-
-
-def split_pieces(c, total, rule):
-    if total == 0:
-        return 1
-    g, p_all = rule
-    return max(1, min(p_all if p_all else (2 * c * g + total) // (2 * total), c // 8, 16))
-
-
 def check_plan(counts, order, g, B, H, nb, block, D=64):
-    """The launch plan, entry for entry.  Every XCD segment holds the entries of the (b,h) pairs
-    with (b*H+h) % 8 == x, longest first, then -1.  With 64-token tiles an entry is an item; with
-    128-token tiles it is a record (item, first list position, kept blocks, w) and an item that is
-    long against a CU's share of the work is cut into pieces by the rule in the header."""
+    """The launch plan is one of many correct ones (how rows are cut and in which order they
+    run is tuning), so it is checked for VALIDITY, after the call has run:
+      * a segment is entries, then only "none" entries; segment x holds items of the (b,h)
+        pairs with (b*H+h) % 8 == x and nothing else;
+      * every item appears: once as a whole (first 0, n = its count, w = -1), or as pieces
+        0..P-1 of P that cover its kept list exactly once, in order, none empty;
+      * the P partial-result slots of a cut item lie inside its segment's pmax slots and no
+        two items share a slot;
+      * arrived[] holds P at the first slot of every cut item (all pieces counted in) and 0
+        everywhere else.
+    Returns {item: [(first, n, k, P), ...]} for the cut items."""
     rows = B * H * nb
-    n_split = 0
+    recs = {}
     for x in range(8):
         seg = order[x]
         valid = seg[:, 0] >= 0
         n = int(valid.sum())
-        assert valid[:n].all() and (seg[n:, 0] == -1).all()
+        assert valid[:n].all(), "entries first, then none"
+        if block == 128:
+            assert (seg[n:] == np.array([-1, 0, 0, -1])).all()
+        else:
+            assert (seg[n:, 0] == -1).all()
         ent = seg[:n]
-        mine = [i for i in range(rows) if (i // nb) % 8 == x]          # ascending item id
-        assert ((ent[:, 0] // nb) % 8 == x).all()
-        if block != 128:
-            assert sorted(ent[:, 0].tolist()) == mine
-            assert (np.diff(counts[ent[:, 0]]) <= 0).all()
+        assert (ent[:, 0] < rows).all() and ((ent[:, 0] // nb) % 8 == x).all()
+        for e in ent.tolist():
+            recs.setdefault(e[0], []).append(tuple(e[1:]))
+    assert sorted(recs) == list(range(rows)), "every item has an entry"
+    if block != 128:
+        assert all(len(r) == 1 for r in recs.values())
+        return {}
+    pmax = g["pmax"]
+    cut, slots_taken = {}, np.zeros(8 * pmax, bool)
+    want_arrived = np.zeros(8 * pmax, np.int32)
+    for item, rs in recs.items():
+        c = int(counts[item])
+        if len(rs) == 1 and rs[0][2] == -1:
+            assert rs[0][:2] == (0, c), (item, rs, c)
             continue
-        most = (B * H + 7) // 8 * nb                                    # items of the fullest XCD
-        if nb <= 64 and most <= 1024 and most * nb <= 8192:
-            # the one-launch planner: the odd rounds of 32 of the first wave (one record per place
-            # of the XCD: 32 CUs x 2 at D = 128, x 4 at D = 64) are stored backwards
-            ent = ent.copy()
-            for lo in range(32, min(n, 32 * (2 if D == 128 else 4)), 64):
-                ent[lo:lo + 32] = ent[lo:lo + 32][::-1].copy()
-        assert (np.diff(ent[:, 2]) <= 0).all()
-        total = int(counts[mine].sum())
-        rule = split_rule(counts[mine], D)
-        want, run = [], 0
-        for it in mine:
-            c = int(counts[it])
-            P = split_pieces(c, total, rule)
-            slot0 = -1
-            if P > 1:
-                if run + P <= g["pmax"]:
-                    slot0 = run
-                run += P
-                if slot0 < 0:
-                    P = 1
-            for k in range(P):
-                b0 = c * k // P
-                w = ((x * g["pmax"] + slot0) << 8 | k << 4 | (P - 1)) if P > 1 else -1
-                want.append((it, b0, c * (k + 1) // P - b0, w))
-            n_split += P > 1
-        assert sorted(map(tuple, ent.tolist())) == sorted(want)
-    return n_split
+        P = len(rs)
+        assert 2 <= P <= 16
+        rs = sorted(rs)
+        x = (item // nb) % 8
+        slot0 = rs[0][2] >> 8
+        pos = 0
+        for k, (first, nblk, w) in enumerate(rs):
+            assert w >= 0 and (w & 15) == P - 1 and ((w >> 4) & 15) == k and (w >> 8) == slot0, (item, rs)
+            assert first == pos and nblk >= 1, (item, rs)
+            pos += nblk
+        assert pos == c, (item, rs, c)
+        assert x * pmax <= slot0 and slot0 + P <= (x + 1) * pmax
+        assert not slots_taken[slot0:slot0 + P].any(), "two items share a partial-result slot"
+        slots_taken[slot0:slot0 + P] = True
+        want_arrived[slot0] = P
+        cut[item] = [(first, nblk, k, P) for k, (first, nblk, w) in enumerate(rs)]
+    np.testing.assert_array_equal(g["arrived"], want_arrived)
+    return cut
 
 
 def test_compaction_is_bit_exact():
@@ -298,7 +287,9 @@ def test_long_rows_are_split_into_pieces_and_merged(D):
     got, ws = run_sparse(q, k, v, mask, block, kv_len, return_ws=True)
     counts, order, _, g = read_plan(ws, B, H, nb, D, block)
     np.testing.assert_array_equal(counts, oracle.kept_tiles(mask, block, kv_len)[0].reshape(-1))
-    assert check_plan(counts, order, g, B, H, nb, block, D) >= 2 * B * H
+    cut = check_plan(counts, order, g, B, H, nb, block, D)
+    long_items = [(b * H + h) * nb + r for b in range(B) for h in range(H) for r in (5, nb - 1)]
+    assert all(it in cut for it in long_items), "the rows that keep every tile are cut into pieces"
     rng = np.random.default_rng(3)
     rows_ = np.stack([rng.integers(B, size=160), rng.integers(H, size=160),
                       rng.choice(np.r_[5 * block:6 * block, (nb - 1) * block:kv_len, 17 * block:18 * block,
@@ -307,28 +298,122 @@ def test_long_rows_are_split_into_pieces_and_merged(D):
     assert_close(got[rows_[:, 0], rows_[:, 1], rows_[:, 2]], ref, "split rows")
 
 
-# ---------------------------------------------------------------- full sizes, sampled rows
-FULL = [("sd3_1024", 1.0), ("sd3_1024", 0.25), ("flux_1024", 1.0), ("flux_1024", 0.5),
-        ("flux_1024", 0.2), ("grpo_sd3", "mixed"), ("flux_2048", 0.1), ("flux_2048", 0.3)]
+# ---------------------------------------------------------------- full sizes
+def per_block_errors(got_bits, ref, block, what):
+    """Beyond the whole-tensor bounds: every (sample, head, query-block) on its own, so that one
+    wrong block (one plan record, one piece of a cut row) cannot hide in the average of millions
+    of good elements."""
+    B, H, N, D = ref.shape
+    g = widen(got_bits)
+    d2 = ((g - ref) ** 2).reshape(B, H, N // block, block * D).sum(-1)
+    r2 = (ref ** 2).reshape(B, H, N // block, block * D).sum(-1)
+    live = r2 > 0
+    rel = np.sqrt(d2[live] / r2[live])
+    worst = np.unravel_index(np.argmax(np.where(live, d2 / np.maximum(r2, 1e-300), 0)), d2.shape)
+    assert rel.max() <= 1e-2, f"{what}: (b, h, query-block) {worst} is off by {rel.max():.3e} (relative Frobenius)"
+    assert (d2[~live] == 0).all(), f"{what}: rows that must be zero are not"
 
 
-@pytest.mark.parametrize("name,density", FULL)
-def test_full_size_sampled_rows(name, density):
-    """The bench's launch configuration at the full workload sizes; the oracle
-    computes a seeded sample of output rows (first/last/boundary/pad rows included)."""
+EVERY = [("sd3_1024", 1.0), ("sd3_1024", 0.25), ("sd3_1024", "total0.25"), ("flux_1024", 1.0),
+         ("flux_1024", 0.5), ("flux_1024", 0.2), ("grpo_sd3", "mixed")]
+
+
+@pytest.mark.parametrize("name,density", EVERY)
+def test_full_size_every_element(name, density):
+    """The workloads at their full sizes, in the launch configuration the bench times, EVERY
+    output element against the oracle: all (sample, head) pairs, all query-blocks, all plan
+    records whatever their kind.  The plan that ran is read back and checked for validity."""
     w = wl.WORKLOADS[name]
     q, k, v = w.qkv(pad_fill="nan")
     mask = w.mask(density)
-    rows = wl.sample_rows(w.B, w.H, w.N, w.kv_len, w.block, 384, seed=w.seed() + 1)
-    got = run_sparse(q, k, v, mask, w.block, w.kv_len)
+    got, ws = run_sparse(q, k, v, mask, w.block, w.kv_len, return_ws=True)
+    ref = oracle.attention(q, k, v, w.kv_len, mask, w.block)
+    assert_close(got, ref, f"{name} d={density} sparse entry")
+    per_block_errors(got, ref, w.block, f"{name} d={density} sparse entry")
+    assert (got[:, :, w.kv_len:] == 0).all()
+    counts, order, index, g = read_plan(ws, w.B, w.H, w.nb, w.D, w.block)
+    np.testing.assert_array_equal(counts, oracle.kept_tiles(mask, w.block, w.kv_len)[0].reshape(-1))
+    cut = check_plan(counts, order, g, w.B, w.H, w.nb, w.block, w.D)
+    print(f"{name} d={density}: {len(cut)} of {w.B * w.H * w.nb} rows ran as pieces")   # every one of them is compared
+    if density == 1.0 or name == "grpo_sd3":
+        mask_is_full = density == 1.0
+        got_d = run_dense(q, k, v, w.kv_len)
+        ref_d = ref if mask_is_full else oracle.attention(q, k, v, w.kv_len)
+        assert_close(got_d, ref_d, f"{name} dense entry")
+        per_block_errors(got_d, ref_d, w.block, f"{name} dense entry")
+        assert (got_d[:, :, w.kv_len:] == 0).all()
+
+
+def stratified_blocks(w, extra, per_head, seed):
+    """Query-blocks to check, per (sample, head): the first and last image block, the blocks at
+    the edge of the local band, every text block, the blocks in `extra` (per pair), then random
+    ones up to per_head."""
+    rng = np.random.Generator(np.random.PCG64(seed))
+    nI = w.nb - w.n_text_blocks
+    out = {}
+    for b in range(w.B):
+        for h in range(w.H):
+            s = {0, 1, 8, 9, nI - 10, nI - 9, nI - 2, nI - 1} | set(range(nI, w.nb)) | set(extra.get((b, h), ()))
+            while len(s) < per_head:
+                s.add(int(rng.integers(w.nb)))
+            out[(b, h)] = sorted(s)
+    return out
+
+
+@pytest.mark.parametrize("density", [0.1, 0.3])
+def test_flux_2048_sparse_stratified(density):
+    """The largest workload (the oracle would need minutes for all of it): the plan is read
+    back and the rows are chosen from it on purpose -- every (sample, head); at least 10 % of
+    the query-blocks of each, among them the first, the last, the band edges, all text blocks
+    and every block whose row was cut into pieces; all 128 rows (all four wavefronts) of each
+    chosen block."""
+    w = wl.WORKLOADS["flux_2048"]
+    q, k, v = w.qkv(pad_fill="nan")
+    mask = w.mask(density)
+    got, ws = run_sparse(q, k, v, mask, w.block, w.kv_len, return_ws=True)
+    counts, order, index, g = read_plan(ws, w.B, w.H, w.nb, w.D, w.block)
+    want_counts, want_index = oracle.kept_tiles(mask, w.block, w.kv_len)
+    np.testing.assert_array_equal(counts, want_counts.reshape(-1))
+    want_index = want_index.reshape(-1, w.nb)
+    for r in range(w.B * w.H * w.nb):
+        np.testing.assert_array_equal(index[r, :counts[r]], want_index[r, :counts[r]])
+    cut = check_plan(counts, order, g, w.B, w.H, w.nb, w.block, w.D)
+    print(f"flux_2048 d={density}: {len(cut)} of {w.B * w.H * w.nb} rows ran as pieces")
+    extra = {}
+    for item in cut:
+        extra.setdefault((item // w.nb // w.H, item // w.nb % w.H), []).append(item % w.nb)
+    per_head = max(14, -(-w.nb // 10))
+    blocks = stratified_blocks(w, extra, per_head, seed=w.seed() + 11)
+    assert len(blocks) == w.B * w.H and all(len(v_) >= 0.10 * w.nb for v_ in blocks.values())
+    assert all(set(extra.get(key, ())) <= set(v_) for key, v_ in blocks.items())
+    rows = np.array([(b, h, i * w.block + r) for (b, h), bl in blocks.items() for i in bl for r in range(w.block)],
+                    np.int32)
     ref = oracle.attention_rows(q, k, v, rows, w.kv_len, mask, w.block)
     sel = got[rows[:, 0], rows[:, 1], rows[:, 2]]
-    assert_close(sel, ref, f"{name} d={density} sparse entry")
-    assert (got[:, :, w.kv_len:] == 0).all()
+    assert_close(sel, ref, f"flux_2048 d={density}")
+    per_block_errors(sel.reshape(1, 1, -1, w.D), ref.reshape(1, 1, -1, w.D), w.block, f"flux_2048 d={density}")
     assert np.isfinite(widen(got)).all()
-    if density == 1.0:
-        got_d = run_dense(q, k, v, w.kv_len)
-        assert_close(got_d[rows[:, 0], rows[:, 1], rows[:, 2]], ref, f"{name} dense entry")
-        # action 0 == all-ones mask, up to summation order (the sparse path splits the key
-        # list between two wavefront groups and merges them)
-        assert_close(got, widen(got_d), f"{name} all-ones vs dense")
+
+
+def test_flux_2048_dense_stratified():
+    """Dense entry at the largest workload: every (sample, head), 8 of the 66 workgroup tiles of
+    256 queries of each (first, last, the one holding the image/text border, random ones), all
+    256 rows (both wavefront groups) of each."""
+    w = wl.WORKLOADS["flux_2048"]
+    q, k, v = w.qkv(pad_fill="nan")
+    got = run_dense(q, k, v, w.kv_len)
+    rng = np.random.Generator(np.random.PCG64(w.seed() + 13))
+    nt = w.N // 256
+    rows = []
+    for h in range(w.H):
+        tiles = {0, nt - 1, (w.N - 512) // 256 - 1, (w.N - 512) // 256}
+        while len(tiles) < 8:
+            tiles.add(int(rng.integers(nt)))
+        assert len(tiles) >= 0.10 * nt
+        rows += [(0, h, t * 256 + r) for t in sorted(tiles) for r in range(256)]
+    rows = np.array(rows, np.int32)
+    ref = oracle.attention_rows(q, k, v, rows, w.kv_len)
+    sel = got[rows[:, 0], rows[:, 1], rows[:, 2]]
+    assert_close(sel, ref, "flux_2048 dense")
+    per_block_errors(sel.reshape(1, 1, -1, w.D), ref.reshape(1, 1, -1, w.D), 256, "flux_2048 dense")
+    assert np.isfinite(widen(got)).all()

@@ -173,6 +173,12 @@ class Workload:
                 return np.ones((self.B, self.H, self.nb, self.nb), np.uint8)
             return mask_bernoulli_diag(self.B, self.H, self.nb, density, seed)
         if self.name in ("sd3_1024", "flux_1024"):
+            if isinstance(density, str) and density.startswith("total"):
+                # the density as a TOTAL over the whole grid, text rows/columns included:
+                # the image x image sub-grid keeps whatever is left after the text tiles
+                nI = self.nb - self.n_text_blocks
+                kept_image = round(float(density[5:]) * self.nb ** 2) - (self.nb ** 2 - nI ** 2)
+                density = max(kept_image, nI) / nI ** 2
             return mask_text_dense(self.B, self.H, self.nb, self.n_text_blocks, density, seed)
         if self.name == "grpo_sd3":
             return mask_text_dense(self.B, self.H, self.nb, self.n_text_blocks, None, seed,
@@ -193,7 +199,7 @@ WORKLOADS = {
     w.name: w for w in [
         Workload("tiny", 1, 2, 256, 256, 64, 64, 0, (1.0, 0.5), 1,
                  "4x4 block grid, Bernoulli(0.5) with diagonal on"),
-        Workload("sd3_1024", 1, 24, 4480, 4429, 64, 128, 3, (1.0, 0.25), 2,
+        Workload("sd3_1024", 1, 24, 4480, 4429, 64, 128, 3, (1.0, 0.25, "total0.25"), 2,
                  "4096 image + 333 text tokens, padded to 35 blocks"),
         Workload("flux_1024", 1, 24, 4608, 4608, 128, 128, 4, (1.0, 0.5, 0.2), 3,
                  "4096 image + 512 text tokens"),
