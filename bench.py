@@ -34,17 +34,32 @@ if ROOT not in sys.path:
 PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA peak (published, no sparsity)
 
 
-def measured_traffic(workload):
+def source_digest():
+    """sha256 of the attention kernels' source: a counter summary under profiles/ names the
+    source it was taken from."""
+    import hashlib
+    path = os.path.join(ROOT, "paper_2509_22323_amd", "csrc", "rapid_attn.hip")
+    return hashlib.sha256(open(path, "rb").read()).hexdigest()
+
+
+def measured_traffic(workload, D):
     """HBM bytes per launch of the dense kernel, from the committed rocprofv3 --pmc summary
-    (FETCH_SIZE and WRITE_SIZE runs scaled by a plain copy); None if there is none."""
-    path = os.path.join(ROOT, "profiles", f"attn_dense_pp_kernel_{workload}.txt")
+    (FETCH_SIZE and WRITE_SIZE runs scaled by a plain copy).  The counters cannot be read from
+    inside this process, so the figure comes from a file: it is reported with the file's name and
+    only if the file says it was taken from the kernel source that is being run now."""
+    name = f"attn_dense_pp_kernel_{workload}.txt"
+    info = {"file": f"profiles/{name}", "kernel_source_sha256": None, "matches_source_in_tree": False}
+    traffic = None
     try:
-        for line in open(path):
+        for line in open(os.path.join(ROOT, "profiles", name)):
             if line.startswith("TRAFFIC_BYTES_PER_LAUNCH="):
-                return int(line.split("=", 1)[1])
+                traffic = int(line.split("=", 1)[1])
+            if line.startswith("KERNEL_SOURCE_SHA256="):
+                info["kernel_source_sha256"] = line.split("=", 1)[1].strip()
     except OSError:
-        pass
-    return None
+        return None, {"file": None}
+    info["matches_source_in_tree"] = info["kernel_source_sha256"] == source_digest()
+    return (traffic if info["matches_source_in_tree"] else None), info
 
 
 def parse():
@@ -64,6 +79,12 @@ def parse():
     ap.add_argument("--no-joint", action="store_true")
     ap.add_argument("--no-mask-select", action="store_true")
     ap.add_argument("--no-trace", action="store_true")
+    ap.add_argument("--no-configs", action="store_true", help="skip the per-config table (all five workloads)")
+    ap.add_argument("--only-attention", action="store_true",
+                    help="time the dense call and the sparse densities of --workload and nothing else "
+                         "(what the per-kernel profiles under profiles/ are taken from)")
+    ap.add_argument("--density", default=None,
+                    help="with --only-attention: time only this nominal density of the sparse entry point")
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain device copy of the Q tensor (known size) so that HBM "
@@ -73,6 +94,9 @@ def parse():
 
 def main():
     args = parse()
+    if args.only_attention:
+        args.no_cpu_baseline = args.no_mfma_probe = args.no_cache_ops = args.no_joint = True
+        args.no_mask_select = args.no_trace = args.no_configs = True
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus above 1 is not supported "
               "(no collectives or sharding are part of it).", file=sys.stderr)
@@ -171,6 +195,7 @@ def main():
     # few microseconds between launches, which is why the timed region above has none inside)
     _, _, ev_min = time_calls(dense_call, min(args.steps, 200), 0)
 
+    traffic, traffic_info = measured_traffic(w.name, w.D)
     out = {
         "metric": "effective TFLOP/s (4*B*H*N^2*D*density), dense joint attention",
         "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
@@ -182,7 +207,7 @@ def main():
         "pct_of_bf16_mfma_peak": round(100.0 * value / PEAK_BF16_TFLOPS, 2),
         "roofline": {"bound": "mfma", "kernel": f"attn_dense_pp_kernel<{w.D}>", "achieved": round(achieved, 2),
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                     "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": measured_traffic(w.name),
+                     "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": traffic, "traffic_source": traffic_info,
                      "algorithmic_bytes": 4 * dq.numel() * 2,
                      "launch_ms_mean": round(ev_mean, 5), "launch_ms_min": round(ev_min, 5)},
     }
@@ -224,6 +249,8 @@ def main():
     if not args.no_sparse:
         sparse = []
         for d in w.densities:
+            if args.density is not None and str(d) != args.density:
+                continue
             mask = w.mask(d)
             eff = wl.effective_density(mask, w.block, w.kv_len)
             dm = torch.from_numpy(mask).cuda()
@@ -255,27 +282,41 @@ def main():
         del segs
 
     # ---- block-mask selection for the Sparse-Attention levels (block means -> softmax -> mass cut):
-    # streams Q and K once (HBM-bound), then one wavefront per mask row
+    # streams Q and K once (HBM-bound), then one wavefront per mask row.  Timed by graph replay (the
+    # host's issue time is out of the way), twice: on ONE set of Q, K, which the 256 MB memory-side
+    # cache then serves, and rotating over enough copies of Q, K that every call reads from HBM.
     if not args.no_mask_select and w.N % w.block == 0 and w.N // w.block <= 2048:
         nbk = w.N // w.block
         sel_mask = torch.empty(w.B, w.H, nbk, nbk, dtype=torch.uint8, device="cuda")
         sel_ws = torch.empty(ra.rapid_mask_select_workspace_bytes(w.B, w.H, w.N, w.D, w.block), dtype=torch.uint8,
                              device="cuda")
         text_start = w.N - 512 if w.N > 1024 else w.N
+        read_bytes = 2 * dq.numel() * 2
+        n_sets = int(-(-600e6 // read_bytes)) + 1
+        qk_sets = [(dq, dk)] + [(dq.clone(), dk.clone()) for _ in range(n_sets - 1)]
+        turn = [0]
         levels = []
         for action in (1, 2, 3):
             tau = ra.rapid_mask_level_tau(action)
             sel_call = lambda: ra.rapid_mask_select(dq, dk, sel_mask, w.block, w.kv_len, text_start, tau, 0.0, sel_ws)
-            _, m_mean, m_min = time_calls(sel_call, 100, 10)
-            levels.append({"action": action, "tau": round(tau, 3), "ms": round(time_graph(sel_call, 20), 5),
-                           "ms_issued_from_python": round(m_mean, 5),
+
+            def sel_rotating():
+                i = turn[0] = (turn[0] + 1) % n_sets
+                ra.rapid_mask_select(qk_sets[i][0], qk_sets[i][1], sel_mask, w.block, w.kv_len, text_start, tau, 0.0,
+                                     sel_ws)
+
+            levels.append({"action": action, "tau": round(tau, 3),
+                           "ms": round(time_graph(sel_rotating, 4 * n_sets), 5),
+                           "ms_inputs_in_memory_side_cache": round(time_graph(sel_call, 20), 5),
                            "kept_fraction_on_this_input": round(float(sel_mask.float().mean()), 4)})
-        read_bytes = 2 * dq.numel() * 2
         gbs = read_bytes / (levels[0]["ms"] * 1e-3) / 1e9
-        out["mask_select"] = {"levels": levels,
+        gbs_c = read_bytes / (levels[0]["ms_inputs_in_memory_side_cache"] * 1e-3) / 1e9
+        out["mask_select"] = {"levels": levels, "qk_sets_rotated": n_sets,
                               "roofline": {"bound": "hbm", "kernel": "block_mean_kernel (+ select_blocks_kernel in the time)",
                                            "achieved": round(gbs, 1), "peak": 8000.0, "unit": "GB/s",
-                                           "frac": round(gbs / 8000.0, 4), "algorithmic_bytes": read_bytes}}
+                                           "frac": round(gbs / 8000.0, 4), "algorithmic_bytes": read_bytes,
+                                           "achieved_inputs_in_memory_side_cache": round(gbs_c, 1)}}
+        del qk_sets
 
     # ---- a scripted action trace of one image (counts as in the paper's appendix: 12-16 steps, 4-8 of
     # them reuse the cache, 2-4 run sparse attention) played against the library: the attention side
@@ -330,7 +371,8 @@ def main():
     if not args.no_cache_ops:
         cache = []
         for label, elems in (("latent of one image: 4096 tokens x 64 channels", 4096 * 64),
-                             (f"hidden states of one layer: {w.N} tokens x 3072 channels", w.N * 3072)):
+                             (f"hidden states of one layer: {w.N} tokens x 3072 channels", w.N * 3072),
+                             (f"hidden states of 8 layers: 8 x {w.N} tokens x 3072 channels", 8 * w.N * 3072)):
             # rotate over enough tensor sets to exceed the 256 MB memory-side cache, so that the
             # large case streams from HBM and not from that cache
             sets = max(1, min(8, int(600e6 // (6 * elems))))
@@ -349,8 +391,9 @@ def main():
                 i = turn[0] = (turn[0] + 1) % sets
                 ra.rapid_cache_store(os_[i], xs[i], ds[i])
 
-            _, r_mean, r_min = time_calls(reuse, 200, 20)
-            _, s_mean, s_min = time_calls(store, 200, 20)
+            # GPU time per call by graph replay (every tensor set visited the same number of times)
+            r_mean = time_graph(reuse, 4 * sets)
+            s_mean = time_graph(store, 4 * sets)
             gbs = 6.0 * elems / (r_mean * 1e-3) / 1e9
             cache.append({"tensor": label, "elements": elems, "tensor_sets_rotated": sets,
                           "reuse_ms": round(r_mean, 5), "store_ms": round(s_mean, 5),
@@ -359,6 +402,75 @@ def main():
                                        "algorithmic_bytes": 6 * elems}})
             del xs, ds, os_
         out["cache_reuse"] = cache
+
+    # ---- all five workloads, dense and at every listed density, in this same process: ms, effective
+    # TFLOP/s, fraction of the bf16 MFMA peak, and the sparse time over (effective density x dense
+    # time).  The headline workload's entry repeats the figures measured above.  With the cpu_baseline
+    # leg on, 128 sampled output rows of every (workload, density) are also checked against the oracle.
+    if not args.no_configs:
+        if not args.no_cpu_baseline:
+            import oracle
+
+        def widen(t):
+            return wl.bf16_bits_to_f32(t.contiguous().view(torch.int16).cpu().numpy().view(np.uint16)).astype(np.float64)
+
+        def config_entry(cw, cq, ck, cv, co, cws, host, dense_ms=None, sparse_done=None):
+            flops = cw.dense_flops()
+            n_calls = lambda ms: int(max(10, min(400, 60.0 / max(ms, 1e-3))))
+            call = lambda: ra.rapid_attn_dense(cq, ck, cv, co, cw.kv_len)
+            if dense_ms is None:
+                _, rough = time_region(call, 5, 3)
+                _, dense_ms = time_region(call, n_calls(rough), 5)
+            entry = {"workload": cw.name, "B": cw.B, "H": cw.H, "N": cw.N, "kv_len": cw.kv_len, "D": cw.D,
+                     "block": cw.block, "dense_gflop": round(flops / 1e9, 2),
+                     "dense": {"ms": round(dense_ms, 5), "tflops": round(flops / (dense_ms * 1e-3) / 1e12, 2),
+                               "frac_of_bf16_mfma_peak": round(flops / (dense_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4)},
+                     "sparse": []}
+            rows = None
+            if not args.no_cpu_baseline:
+                rows = wl.sample_rows(cw.B, cw.H, cw.N, cw.kv_len, cw.block, 128, seed=cw.seed() + 5)
+                call()
+                got = widen(co)[rows[:, 0], rows[:, 1], rows[:, 2]]
+                err = np.abs(got - oracle.attention_rows(host[0], host[1], host[2], rows, cw.kv_len))
+                entry["dense"]["oracle_check_128_rows"] = {"max_abs": float(f"{err.max():.3e}"),
+                                                           "mean_abs": float(f"{err.mean():.3e}")}
+            for d in cw.densities:
+                mask = cw.mask(d)
+                eff = wl.effective_density(mask, cw.block, cw.kv_len)
+                dm = torch.from_numpy(mask).cuda()
+                scall = lambda: ra.rapid_attn_block_sparse(cq, ck, cv, co, dm, cw.block, cw.kv_len, 0.0, cws)
+                done = None if sparse_done is None else [x for x in sparse_done if x["density_nominal"] == d]
+                if done:
+                    s_ms = done[0]["ms"]
+                else:
+                    _, rough = time_region(scall, 5, 3)
+                    _, s_ms = time_region(scall, n_calls(rough), 5)
+                e = {"density_nominal": d, "density_effective": round(eff, 4), "ms": round(s_ms, 5),
+                     "eff_tflops": round(flops * eff / (s_ms * 1e-3) / 1e12, 2),
+                     "time_over_density_x_dense": round(s_ms / (eff * dense_ms), 3)}
+                if rows is not None:
+                    scall()
+                    got = widen(co)[rows[:, 0], rows[:, 1], rows[:, 2]]
+                    err = np.abs(got - oracle.attention_rows(host[0], host[1], host[2], rows, cw.kv_len, mask, cw.block))
+                    e["oracle_check_128_rows"] = {"max_abs": float(f"{err.max():.3e}"), "mean_abs": float(f"{err.mean():.3e}")}
+                entry["sparse"].append(e)
+            return entry
+
+        configs = []
+        for name in ("tiny", "sd3_1024", "flux_1024", "grpo_sd3", "flux_2048"):
+            cw = wl.WORKLOADS[name]
+            if name == w.name:
+                configs.append(config_entry(w, dq, dk, dv, do, ws, (q, k, v), dense_ms=ev_mean,
+                                            sparse_done=out.get("sparse")))
+                continue
+            host = cw.qkv()
+            cq, ck, cv = (dev(x) for x in host)
+            co = torch.empty_like(cq)
+            cws = torch.empty(ra.rapid_attn_workspace_bytes(cw.B, cw.H, cw.N, cw.D, cw.block), dtype=torch.uint8,
+                              device="cuda")
+            configs.append(config_entry(cw, cq, ck, cv, co, cws, host))
+            del cq, ck, cv, co, cws, host
+        out["configs"] = configs
 
     # ---- the oracle on this machine's host cores, bounded sample of rows of the same workload
     if not args.no_cpu_baseline:
