@@ -49,6 +49,11 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 
+// Whether the common path of the softmax computes no row maximum (softmax_tile).  At D = 64 the
+// vector unit is the busiest one (half as many MFMA cycles per score as at D = 128) and every
+// instruction taken out of the softmax phase shows; at D = 128 it made no difference.
+template <int D> struct Optimistic { static constexpr bool value = D == 64; };
+
 constexpr int KT = 64;          // keys per LDS tile
 constexpr int XCDS = 8;         // L2 domains the dispatcher deals workgroups over
 constexpr int DENSE_QT = 256;    // query rows per workgroup on the dense path
@@ -672,7 +677,7 @@ __device__ __forceinline__ void issue_tile(const Rows& src, int key0, int kv_len
 }
 
 struct SoftmaxState {
-    float m;      // max used for the exponent (raw score units); same in both lane halves
+    float m;      // reference of the exponents, in units of scale * log2(e); same in both lane halves
     float l;      // this lane's partial sum of probabilities
 };
 
@@ -690,13 +695,13 @@ struct SoftmaxState {
 // returns data in order, so "lgkmcnt(N)" = everything but the newest N requests has
 // arrived; the counter has 4 bits, which bounds PD (at most 15 requests in flight).
 // ---------------------------------------------------------------------------
-template <int D>
+template <int D, int PD_>
 struct TileItems {
     static constexpr int DB = D / 32, KS = D / 16;
     static constexpr int NPV = 4 * DB;
     static constexpr int NQK = 2 * KS;
     static constexpr int NI = NPV + NQK;
-    static constexpr int PD = 6;
+    static constexpr int PD = PD_;             // how many items ahead the LDS reads are requested
     static constexpr int NBUF = PD + 1;
     static constexpr int reads(int i) { return i < NPV ? 2 : 1; }
     // LDS requests of the items after i that are in flight while item i is awaited
@@ -708,20 +713,20 @@ struct TileItems {
     }
 };
 
-template <int D>
+template <int D, int PD>
 struct TileCtx {
     unsigned vaddr[D / 32];                    // LDS byte address of this lane's transpose-read patch, per O^T block
     unsigned kbase;                            // LDS byte address of row n of the K tile
     unsigned kxor;                             // (h ^ swz_k(n)) << 4: chunk (2t+h) ^ swz == (2t) ^ (kxor >> 4)
-    u32x2 lo[TileItems<D>::NBUF];              // item i lives in slot i % NBUF
-    u32x2 hi[TileItems<D>::NBUF];
-    u32x4 kf[TileItems<D>::NBUF];
+    u32x2 lo[TileItems<D, PD>::NBUF];              // item i lives in slot i % NBUF
+    u32x2 hi[TileItems<D, PD>::NBUF];
+    u32x4 kf[TileItems<D, PD>::NBUF];
 };
 
-template <int D, int I>
-__device__ __forceinline__ void item_request(TileCtx<D>& c)
+template <int D, int PD, int I>
+__device__ __forceinline__ void item_request(TileCtx<D, PD>& c)
 {
-    typedef TileItems<D> TI;
+    typedef TileItems<D, PD> TI;
     constexpr int RB = Geo<D>::ROW_BYTES;
     constexpr int slot = I % TI::NBUF;
     if constexpr (I < TI::NPV) {
@@ -739,10 +744,10 @@ __device__ __forceinline__ void item_request(TileCtx<D>& c)
 
 // Wait for item I; LAST = end of the run of items whose requests may be in flight.  The
 // fragment is an in/out operand so that its use is ordered after the wait.
-template <int D, int I, int LAST>
-__device__ __forceinline__ void item_wait(TileCtx<D>& c)
+template <int D, int PD, int I, int LAST>
+__device__ __forceinline__ void item_wait(TileCtx<D, PD>& c)
 {
-    typedef TileItems<D> TI;
+    typedef TileItems<D, PD> TI;
     constexpr int slot = I % TI::NBUF;
     constexpr int N = TI::newer(I, LAST);
     static_assert(N + TI::reads(I) <= 15, "lgkmcnt is a 4-bit counter");
@@ -750,11 +755,11 @@ __device__ __forceinline__ void item_wait(TileCtx<D>& c)
     else asm volatile("s_waitcnt lgkmcnt(%1)" : "+v"(c.kf[slot]) : "i"(N));
 }
 
-template <int D, int I>
-__device__ __forceinline__ void item_mfma(const TileCtx<D>& c, const bf16x8 (&pb)[4], const bf16x8 (&qf)[D / 16],
+template <int D, int PD, int I>
+__device__ __forceinline__ void item_mfma(const TileCtx<D, PD>& c, const bf16x8 (&pb)[4], const bf16x8 (&qf)[D / 16],
                                           f32x16 (&acc)[D / 32], f32x16 (&st)[2])
 {
-    typedef TileItems<D> TI;
+    typedef TileItems<D, PD> TI;
     constexpr int slot = I % TI::NBUF;
     if constexpr (I < TI::NPV) {
         constexpr int g = I / TI::DB, db = I % TI::DB;
@@ -762,6 +767,7 @@ __device__ __forceinline__ void item_mfma(const TileCtx<D>& c, const bf16x8 (&pb
         acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, both), pb[g], acc[db], 0, 0, 0);
     } else {
         constexpr int t = (I - TI::NPV) / 2, rb = (I - TI::NPV) % 2;
+        // the first k-step starts from -m: the tile arrives as exponent differences
         f32x16 cin = st[rb];
         if constexpr (t == 0) {                            // first k-step starts from zero
 #pragma unroll
@@ -772,25 +778,25 @@ __device__ __forceinline__ void item_mfma(const TileCtx<D>& c, const bf16x8 (&pb
 }
 
 // Request the first PD items of the run [FROM, TO).
-template <int D, int FROM, int TO, int I = FROM>
-__device__ __forceinline__ void items_prefetch(TileCtx<D>& c)
+template <int D, int PD, int FROM, int TO, int I = FROM>
+__device__ __forceinline__ void items_prefetch(TileCtx<D, PD>& c)
 {
-    if constexpr (I < TO && I < FROM + TileItems<D>::PD) {
-        item_request<D, I>(c);
-        items_prefetch<D, FROM, TO, I + 1>(c);
+    if constexpr (I < TO && I < FROM + PD) {
+        item_request<D, PD, I>(c);
+        items_prefetch<D, PD, FROM, TO, I + 1>(c);
     }
 }
 
-// Issue items [I, TO); items_prefetch<D, I, TO> must have been called before.
-template <int D, int I, int TO>
-__device__ __forceinline__ void items_run(TileCtx<D>& c, const bf16x8 (&pb)[4], const bf16x8 (&qf)[D / 16],
+// Issue items [I, TO); items_prefetch<D, PD, I, TO> must have been called before.
+template <int D, int PD, int I, int TO>
+__device__ __forceinline__ void items_run(TileCtx<D, PD>& c, const bf16x8 (&pb)[4], const bf16x8 (&qf)[D / 16],
                                           f32x16 (&acc)[D / 32], f32x16 (&st)[2])
 {
     if constexpr (I < TO) {
-        if constexpr (I + TileItems<D>::PD < TO) item_request<D, I + TileItems<D>::PD>(c);
-        item_wait<D, I, TO>(c);
-        item_mfma<D, I>(c, pb, qf, acc, st);
-        items_run<D, I + 1, TO>(c, pb, qf, acc, st);
+        if constexpr (I + PD < TO) item_request<D, PD, I + PD>(c);
+        item_wait<D, PD, I, TO>(c);
+        item_mfma<D, PD, I>(c, pb, qf, acc, st);
+        items_run<D, PD, I + 1, TO>(c, pb, qf, acc, st);
     }
 }
 
@@ -798,8 +804,8 @@ __device__ __forceinline__ void items_run(TileCtx<D>& c, const bf16x8 (&pb)[4], 
 //   K: lane (n, h) reads row n (+32 rb), logical chunk 2t + h of k-step t.
 //   V: within a 16-lane group, lane j points at row j/4, columns 4 (j%4)..+3 of a 4 x 16
 //      patch of the transpose read and lane i receives column i; lane half h covers rows +4h.
-template <int D>
-__device__ __forceinline__ void k_addresses(const char* lds_k, int n, int h, TileCtx<D>& c)
+template <int D, int PD>
+__device__ __forceinline__ void k_addresses(const char* lds_k, int n, int h, TileCtx<D, PD>& c)
 {
     typedef Geo<D> G;
     c.kbase = (unsigned)(size_t)LDS_PTR(const char, lds_k) + n * G::ROW_BYTES;
@@ -832,59 +838,81 @@ __device__ __forceinline__ void mask_tail(f32x16 (&st)[2], int key0, int kv_len,
 }
 
 // Online softmax of one tile (one query per lane; the two lane halves hold disjoint keys).
-// Updates the running reference max / partial sum, rescales the accumulators when the
-// reference moves, and leaves the probabilities as bf16 MFMA operands:
-// pb[2 rb + t] = keys 16t + {4h..4h+3, 8+4h..8+4h+3} of row block rb.
+// Probabilities are exp2(c * s - m) with c = scale * log2(e) and a per-query reference m (kept in
+// exponent units); any m gives the same quotient acc / l, and bf16 and fp32 share their exponent
+// range, so m need not be the running maximum.  Two ways to keep it in range:
+//   lazy (D = 128): the tile's maximum is computed, and m moves up to it only when it lies more
+//     than 8 above m (probabilities stay below 2^8);
+//   optimistic (D = 64): no maximum on the common path.  m comes from the first tile and moves
+//     only when a later tile's probabilities get large: their sum, which is needed anyway,
+//     exceeds 2^60 (or is not a number).  Then the tile's maximum becomes the reference and the
+//     tile's probabilities are computed again.
+// When m moves, l and the accumulators are rescaled.  Leaves the probabilities as bf16 MFMA
+// operands: pb[2 rb + t] = keys 16t + {4h..4h+3, 8+4h..8+4h+3} of row block rb.
 template <int D>
 __device__ __forceinline__ void softmax_tile(const f32x16 (&st)[2], f32x16 (&acc)[D / 32], SoftmaxState& st_,
-                                             float c, float tau, bf16x8 (&pb)[4])
+                                             float c, bool first, bf16x8 (&pb)[4])
 {
     constexpr int DB = D / 32;
-    float mx = fmaxf(st[0][0], st[1][0]);
+    // The row sum adds up the probabilities two per instruction (v_dot2 of the bf16 pair against
+    // 1.0): it is then over the probabilities as rounded to bf16, the weights the PV product applies.
+    typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+    bf16x2 ones;
+    ones[0] = (__bf16)1.0f;
+    ones[1] = (__bf16)1.0f;
+    auto probabilities = [&]() -> float {
+        float rs0 = 0.f, rs1 = 0.f;
 #pragma unroll
-    for (int i = 1; i < 16; ++i) mx = fmaxf(fmaxf(mx, st[0][i]), st[1][i]);
-    {
+        for (int g = 0; g < 4; ++g) {
+            const int rb = g >> 1, t = g & 1;
+#pragma unroll
+            for (int i = 0; i < 8; i += 2) {
+                bf16x2 pr;
+                pr[0] = (__bf16)__builtin_amdgcn_exp2f(__builtin_fmaf(st[rb][8 * t + i], c, -st_.m));
+                pr[1] = (__bf16)__builtin_amdgcn_exp2f(__builtin_fmaf(st[rb][8 * t + i + 1], c, -st_.m));
+                pb[g][i] = pr[0];
+                pb[g][i + 1] = pr[1];
+                if (i & 2) rs1 = __builtin_amdgcn_fdot2_f32_bf16(pr, ones, rs1, false);
+                else rs0 = __builtin_amdgcn_fdot2_f32_bf16(pr, ones, rs0, false);
+            }
+        }
+        return rs0 + rs1;
+    };
+    // the tile's largest exponent relative to m (on the first tile: the exponent itself)
+    auto tile_max = [&]() -> float {
+        float mx = fmaxf(st[0][0], st[1][0]);
+#pragma unroll
+        for (int i = 1; i < 16; ++i) mx = fmaxf(fmaxf(mx, st[0][i]), st[1][i]);
         auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(mx), __float_as_uint(mx), false, false);
         mx = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
+        return first ? mx * c : __builtin_fmaf(mx, c, -st_.m);
+    };
+    float rs = 0.f, mx = 0.f;
+    bool move = first;
+    if constexpr (Optimistic<D>::value) {
+        if (!first) {
+            rs = probabilities();
+            move = __builtin_amdgcn_ballot_w64(!(rs <= 0x1p60f)) != 0ull;     // also true for inf and NaN
+        }
+        if (move) mx = tile_max();
+    } else {
+        mx = tile_max();
+        if (!first) move = __builtin_amdgcn_ballot_w64(mx > 8.0f) != 0ull;
     }
-    // Lazy rescale: keep the old reference max while the new one exceeds it by at most
-    // tau (probabilities then stay below 2^8); any reference gives the same quotient.
-    if (__builtin_amdgcn_ballot_w64(mx > st_.m + tau) != 0ull) {
-        const float m_new = fmaxf(st_.m, mx);              // finite: every visited tile has a valid key
-        const float alpha = __builtin_amdgcn_exp2f((st_.m - m_new) * c);
-        st_.m = m_new;
+    if (move) {
+        // mx is finite: every visited tile has a valid key.  On the first tile nothing has been
+        // accumulated yet; later the reference only moves up.
+        const float delta = first ? mx : fmaxf(mx, 0.f);
+        const float alpha = first ? 1.0f : __builtin_amdgcn_exp2f(-delta);
+        st_.m = first ? mx : st_.m + delta;
         st_.l *= alpha;
 #pragma unroll
         for (int i = 0; i < DB; ++i)
 #pragma unroll
             for (int j = 0; j < 16; ++j) acc[i][j] *= alpha;
     }
-    const float mc = st_.m * c;
-    float rs0 = 0.f, rs1 = 0.f;
-    // The row sum adds up the probabilities two per instruction (v_dot2 of the bf16 pair
-    // against 1.0): the softmax phase is the one the slots wait for.  The sum is then over the
-    // probabilities as rounded to bf16, the weights the PV product really applies.
-    typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
-    bf16x2 ones;
-    ones[0] = (__bf16)1.0f;
-    ones[1] = (__bf16)1.0f;
-#pragma unroll
-    for (int g = 0; g < 4; ++g) {
-        const int rb = g >> 1, t = g & 1;
-#pragma unroll
-        for (int i = 0; i < 8; i += 2) {
-            const float e0 = __builtin_amdgcn_exp2f(__builtin_fmaf(st[rb][8 * t + i], c, -mc));
-            const float e1 = __builtin_amdgcn_exp2f(__builtin_fmaf(st[rb][8 * t + i + 1], c, -mc));
-            bf16x2 pr;
-            pr[0] = (__bf16)e0;
-            pr[1] = (__bf16)e1;
-            pb[g][i] = pr[0];
-            pb[g][i + 1] = pr[1];
-            if (i & 2) rs1 = __builtin_amdgcn_fdot2_f32_bf16(pr, ones, rs1, false);
-            else rs0 = __builtin_amdgcn_fdot2_f32_bf16(pr, ones, rs0, false);
-        }
-    }
-    st_.l += rs0 + rs1;
+    if (!Optimistic<D>::value || move) rs = probabilities();
+    st_.l += rs;
 }
 
 // Epilogue: O = acc / l as bf16.  Register 4j+r of block db holds d = 32 db + 8 j + 4 h + r
@@ -1050,7 +1078,11 @@ template <int D>
 __device__ __forceinline__ void dense_item(const AttnParams& p, char* lds, int bh, int q0)
 {
     typedef Geo<D> G;
-    typedef TileItems<D> TI;
+    // How far ahead the LDS reads run (TileItems).  At D = 64 four wavefronts share a SIMD on 128
+    // registers each; the depth is the largest at which this kernel keeps everything in registers
+    // (a few values in scratch memory inside the loop cost 4-8 %); the other wavefronts cover the latency.
+    constexpr int PD = D == 64 ? 2 : 6;
+    typedef TileItems<D, PD> TI;
     constexpr int NW = 8, KS = D / 16, DB = D / 32;
     constexpr int LPT = 2 * G::LOADS / NW;        // copy instructions per wavefront per tile (K + V), all copying
     auto k_stage = [&](int t) -> char* { return lds + (t & 3) * G::TILE_BYTES; };
@@ -1104,7 +1136,6 @@ __device__ __forceinline__ void dense_item(const AttnParams& p, char* lds, int b
     SoftmaxState sm;
     sm.m = -INFINITY;
     sm.l = 0.f;
-    const float tau = 8.0f / p.c;                 // 2^8 head-room on the probabilities
     const int tr_row = (lane & 15) >> 2;
     const int tr_col = ((lane & 3) << 2) + (((lane >> 4) & 1) << 4);
 
@@ -1114,12 +1145,12 @@ __device__ __forceinline__ void dense_item(const AttnParams& p, char* lds, int b
     __syncthreads();
     if (group == 1) __syncthreads();              // group 1 runs one barrier behind
 
-    TileCtx<D> ctx;
+    TileCtx<D, PD> ctx;
     bf16x8 pb[4];
     f32x16 st[2];
     k_addresses<D>(k_stage(0), n, h, ctx);
-    items_prefetch<D, TI::NPV, TI::NI>(ctx);
-    items_run<D, TI::NPV, TI::NI>(ctx, pb, qf, acc, st);   // S_0
+    items_prefetch<D, PD, TI::NPV, TI::NI>(ctx);
+    items_run<D, PD, TI::NPV, TI::NI>(ctx, pb, qf, acc, st);   // S_0
     mask_tail(st, 0, kv_len, h);
 
     // Where the tile copies are issued.  At D = 128 the A phase is the critical one (measured per
@@ -1153,9 +1184,9 @@ __device__ __forceinline__ void dense_item(const AttnParams& p, char* lds, int b
             }
         }
         v_addresses<D>(v_stage(j), h, tr_row, tr_col, ctx.vaddr);
-        softmax_tile<D>(st, acc, sm, p.c, tau, pb);
+        softmax_tile<D>(st, acc, sm, p.c, j == 0, pb);
         pin_in_phase(pb, sm.l);
-        items_prefetch<D, 0, TI::NI>(ctx);        // first V_j^T fragments of A(j)
+        items_prefetch<D, PD, 0, TI::NI>(ctx);        // first V_j^T fragments of A(j)
         if constexpr (COPY_IN_B) {
             // my group's tile j+1 has landed; its tiles j+2 and j+3 may still be on their way
             // (tiles 0..2 came with the prologue: in the loop tile t is issued in B(t-3))
@@ -1177,7 +1208,7 @@ __device__ __forceinline__ void dense_item(const AttnParams& p, char* lds, int b
         // PV(j) then QK(j+1) as one stream.  For the last tile the QK half re-reads a
         // landed stage and its result is never used.
         k_addresses<D>(k_stage((j + 1 < T) ? j + 1 : j), n, h, ctx);
-        items_run<D, 0, TI::NI>(ctx, pb, qf, acc, st);
+        items_run<D, PD, 0, TI::NI>(ctx, pb, qf, acc, st);
         mask_tail(st, (j + 1) * KT, kv_len, h);
         __builtin_amdgcn_s_setprio(0);
     }
@@ -1234,7 +1265,8 @@ template <int D, int WPG>
 __global__ __launch_bounds__(128 * WPG, (D == 64 && WPG == 4 ? 4 : 2)) void attn_sparse_pp_kernel(const AttnParams p)
 {
     typedef Geo<D> G;
-    typedef TileItems<D> TI;
+    constexpr int PD = 6;
+    typedef TileItems<D, PD> TI;
     constexpr int NW = 2 * WPG, QT = 32 * WPG, KS = D / 16, DB = D / 32;
     constexpr int NSK = 4, NSV = 5;
     constexpr int LPT = 2 * G::LOADS / NW;        // copy instructions per wavefront per slot (K + V)
@@ -1310,7 +1342,6 @@ __global__ __launch_bounds__(128 * WPG, (D == 64 && WPG == 4 ? 4 : 2)) void attn
     SoftmaxState sm;
     sm.m = -INFINITY;
     sm.l = 0.f;
-    const float tau = 8.0f / p.c;
     const int tr_row = (lane & 15) >> 2;
     const int tr_col = ((lane & 3) << 2) + (((lane >> 4) & 1) << 4);
     wait_vmcnt<0>();
@@ -1331,7 +1362,7 @@ __global__ __launch_bounds__(128 * WPG, (D == 64 && WPG == 4 ? 4 : 2)) void attn
         vst_issue = (vst_issue == NSV - 1) ? 0 : vst_issue + 1;
     };
 
-    TileCtx<D> ctx;
+    TileCtx<D, PD> ctx;
     bf16x8 pb[4];
     f32x16 st[2];
 
@@ -1340,8 +1371,8 @@ __global__ __launch_bounds__(128 * WPG, (D == 64 && WPG == 4 ? 4 : 2)) void attn
     if (t < T) {                                  // slot t: S_t on its own
         slot_begin();
         k_addresses<D>(k_stage(t), n, h, ctx);
-        items_prefetch<D, TI::NPV, TI::NI>(ctx);
-        items_run<D, TI::NPV, TI::NI>(ctx, pb, qf, acc, st);
+        items_prefetch<D, PD, TI::NPV, TI::NI>(ctx);
+        items_run<D, PD, TI::NPV, TI::NI>(ctx, pb, qf, acc, st);
         mask_tail(st, kq[0], kv_len, h);
         slot_end();
     }
@@ -1349,16 +1380,16 @@ __global__ __launch_bounds__(128 * WPG, (D == 64 && WPG == 4 ? 4 : 2)) void attn
         // ---- slot t+1: B(t)
         slot_begin();
         v_addresses<D>(lds + (NSK + vst_use) * G::TILE_BYTES, h, tr_row, tr_col, ctx.vaddr);
-        softmax_tile<D>(st, acc, sm, p.c, tau, pb);
+        softmax_tile<D>(st, acc, sm, p.c, t == group, pb);
         pin_in_phase(pb, sm.l);
-        items_prefetch<D, 0, TI::NI>(ctx);        // first V_t^T fragments of A(t)
+        items_prefetch<D, PD, 0, TI::NI>(ctx);        // first V_t^T fragments of A(t)
         slot_end();
         // ---- slot t+2: A(t)
         __builtin_amdgcn_s_setprio(3);
         slot_begin();
         // (without a tile t+2 the QK half re-reads K_t, which is landed, and is dropped)
         k_addresses<D>(k_stage((t + 2 < T) ? t + 2 : t), n, h, ctx);
-        items_run<D, 0, TI::NI>(ctx, pb, qf, acc, st);
+        items_run<D, PD, 0, TI::NI>(ctx, pb, qf, acc, st);
         mask_tail(st, kq[0], kv_len, h);
         __builtin_amdgcn_s_setprio(0);
         slot_end();
@@ -1389,8 +1420,8 @@ __global__ __launch_bounds__(128 * WPG, (D == 64 && WPG == 4 ? 4 : 2)) void attn
         const float m1 = mlbuf[(wq * 64 + lane) * 2];
         const float l1 = mlbuf[(wq * 64 + lane) * 2 + 1];
         const float m = fmaxf(sm.m, m1);                          // group 0 always has tile 0: finite
-        const float a0 = __builtin_amdgcn_exp2f((sm.m - m) * p.c);
-        const float a1 = __builtin_amdgcn_exp2f((m1 - m) * p.c);  // 0 if group 1 had no tile
+        const float a0 = __builtin_amdgcn_exp2f(sm.m - m);
+        const float a1 = __builtin_amdgcn_exp2f(m1 - m);         // 0 if group 1 had no tile
 #pragma unroll
         for (int db = 0; db < DB; ++db)
 #pragma unroll
@@ -1434,7 +1465,8 @@ template <int D>
 __global__ __launch_bounds__(256, (D == 64 ? 4 : 2)) void attn_sparse_sg_kernel(const AttnParams p)
 {
     typedef Geo<D> G;
-    typedef TileItems<D> TI;
+    constexpr int PD = D == 64 ? 3 : 6;           // see dense_item
+    typedef TileItems<D, PD> TI;
     constexpr int NW = 4, QT = 128, KS = D / 16, DB = D / 32;
     constexpr int LPT = G::LOADS / NW;            // copy instructions per wavefront per tile (K or V)
 
@@ -1502,7 +1534,6 @@ __global__ __launch_bounds__(256, (D == 64 ? 4 : 2)) void attn_sparse_sg_kernel(
     SoftmaxState sm;
     sm.m = -INFINITY;
     sm.l = 0.f;
-    const float tau = 8.0f / p.c;
     const int tr_row = (lane & 15) >> 2;
     const int tr_col = ((lane & 3) << 2) + (((lane >> 4) & 1) << 4);
     if (1 < T) wait_vmcnt<2 * LPT>();
@@ -1511,12 +1542,12 @@ __global__ __launch_bounds__(256, (D == 64 ? 4 : 2)) void attn_sparse_sg_kernel(
     q_arrived<D>(qraw, qvalid, qf);
     __syncthreads();
 
-    TileCtx<D> ctx;
+    TileCtx<D, PD> ctx;
     bf16x8 pb[4];
     f32x16 st[2];
     k_addresses<D>(k_stage(0), n, h, ctx);
-    items_prefetch<D, TI::NPV, TI::NI>(ctx);
-    items_run<D, TI::NPV, TI::NI>(ctx, pb, qf, acc, st);   // S_0
+    items_prefetch<D, PD, TI::NPV, TI::NI>(ctx);
+    items_run<D, PD, TI::NPV, TI::NI>(ctx, pb, qf, acc, st);   // S_0
     mask_tail(st, key0, kv_len, h);
     if (1 < T) wait_vmcnt<LPT>();                 // V_0 landed (K_1 may still be on its way)
     else wait_vmcnt<0>();
@@ -1528,9 +1559,9 @@ __global__ __launch_bounds__(256, (D == 64 ? 4 : 2)) void attn_sparse_sg_kernel(
         if (j + 1 < T) issue_tile<D, NW, true>(V, kn1, kv_len, v_stage(j + 1), wave, lane);
         if (j + 2 < T) issue_tile<D, NW, false>(K, kn2, kv_len, k_stage(j), wave, lane);
         v_addresses<D>(v_stage(j), h, tr_row, tr_col, ctx.vaddr);
-        softmax_tile<D>(st, acc, sm, p.c, tau, pb);
+        softmax_tile<D>(st, acc, sm, p.c, j == 0, pb);
         pin_in_phase(pb, sm.l);
-        items_prefetch<D, 0, TI::NI>(ctx);        // first V_j^T fragments of A(j)
+        items_prefetch<D, PD, 0, TI::NI>(ctx);        // first V_j^T fragments of A(j)
         if (j + 2 < T) wait_vmcnt<2 * LPT>();     // K_{j+1} landed
         else if (j + 1 < T) wait_vmcnt<LPT>();
         else wait_vmcnt<0>();
@@ -1540,7 +1571,7 @@ __global__ __launch_bounds__(256, (D == 64 ? 4 : 2)) void attn_sparse_sg_kernel(
         // K_j, which is still in its stage, and its result is never used)
         __builtin_amdgcn_s_setprio(3);
         k_addresses<D>(k_stage((j + 1 < T) ? j + 1 : j), n, h, ctx);
-        items_run<D, 0, TI::NI>(ctx, pb, qf, acc, st);
+        items_run<D, PD, 0, TI::NI>(ctx, pb, qf, acc, st);
         mask_tail(st, kn1, kv_len, h);
         __builtin_amdgcn_s_setprio(0);
         if (j + 2 < T) wait_vmcnt<LPT>();         // V_{j+1} landed
@@ -1609,7 +1640,7 @@ __global__ __launch_bounds__(256, (D == 64 ? 4 : 2)) void attn_sparse_sg_kernel(
     float l = 0.f;
     for (int k = 0; k < P; ++k) {
         const u64 ml = __hip_atomic_load(slot_ml(k), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        const float a = __builtin_amdgcn_exp2f((__uint_as_float((unsigned)ml) - m) * p.c);
+        const float a = __builtin_amdgcn_exp2f(__uint_as_float((unsigned)ml) - m);
         l += __uint_as_float((unsigned)(ml >> 32)) * a;
         const u64* pacc = slot_acc(k);
 #pragma unroll
