@@ -71,6 +71,8 @@ def parse():
                     help="before the warm-up steps, keep the GPU under the same load for this long: after "
                          "idling, its clock takes some tens of milliseconds to come up (the first ~100 "
                          "calls run ~13 %% slower)")
+    ap.add_argument("--leg-ramp-ms", type=float, default=40.0,
+                    help="the same before every further timed leg (sparse densities, joint layout, other workloads)")
     ap.add_argument("--workload", default="flux_1024")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-sparse", action="store_true")
@@ -143,6 +145,15 @@ def main():
         durs = [a.elapsed_time(b) for a, b in ev]
         return wall, float(np.mean(durs)), float(np.min(durs))
 
+    def ramp(fn, ms):
+        """Keep the GPU under the load of `fn` for `ms`: while the host prepares the next input
+        the GPU idles and its clock drops; the first ~25 ms of calls after that run ~13 % slower."""
+        t0 = time.perf_counter()
+        while (time.perf_counter() - t0) * 1e3 < ms:
+            for _ in range(8):
+                fn()
+            torch.cuda.synchronize()
+
     def time_graph(fn, calls, replays=20):
         """GPU ms per call with the host out of the way: `calls` calls captured in one HIP graph,
         replayed; for calls so short that issuing them from Python takes longer than running them."""
@@ -155,8 +166,7 @@ def main():
         with torch.cuda.graph(graph):
             for _ in range(calls):
                 fn()
-        for _ in range(3):
-            graph.replay()
+        ramp(graph.replay, args.leg_ramp_ms)
         a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         torch.cuda.synchronize()
         a.record()
@@ -166,9 +176,11 @@ def main():
         torch.cuda.synchronize()
         return a.elapsed_time(b) / (replays * calls)
 
-    def time_region(fn, steps, warmup):
+    def time_region(fn, steps, warmup, ramp_ms=None):
         """The timed region proper: `steps` calls back to back, nothing else in the stream; wall ms
-        per step between synchronisations and HIP-event ms per step over the same region."""
+        per step between synchronisations and HIP-event ms per step over the same region.  Every
+        leg is preceded by its own ramp (see ramp)."""
+        ramp(fn, args.leg_ramp_ms if ramp_ms is None else ramp_ms)
         for _ in range(warmup):
             fn()
         a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -188,7 +200,7 @@ def main():
         for _ in range(20):
             dense_call()
         torch.cuda.synchronize()
-    wall_ms, ev_mean = time_region(dense_call, args.steps, args.warmup)
+    wall_ms, ev_mean = time_region(dense_call, args.steps, args.warmup, ramp_ms=0.0)
     value = dense_flops / (wall_ms * 1e-3) / 1e12
     achieved = dense_flops / (ev_mean * 1e-3) / 1e12
     # one launch at a time between its own pair of events (the events themselves open a gap of a
@@ -420,7 +432,7 @@ def main():
             call = lambda: ra.rapid_attn_dense(cq, ck, cv, co, cw.kv_len)
             if dense_ms is None:
                 _, rough = time_region(call, 5, 3)
-                _, dense_ms = time_region(call, n_calls(rough), 5)
+                _, dense_ms = time_region(call, n_calls(rough), 5, ramp_ms=0.0)
             entry = {"workload": cw.name, "B": cw.B, "H": cw.H, "N": cw.N, "kv_len": cw.kv_len, "D": cw.D,
                      "block": cw.block, "dense_gflop": round(flops / 1e9, 2),
                      "dense": {"ms": round(dense_ms, 5), "tflops": round(flops / (dense_ms * 1e-3) / 1e12, 2),
@@ -444,7 +456,7 @@ def main():
                     s_ms = done[0]["ms"]
                 else:
                     _, rough = time_region(scall, 5, 3)
-                    _, s_ms = time_region(scall, n_calls(rough), 5)
+                    _, s_ms = time_region(scall, n_calls(rough), 5, ramp_ms=0.0)
                 e = {"density_nominal": d, "density_effective": round(eff, 4), "ms": round(s_ms, 5),
                      "eff_tflops": round(flops * eff / (s_ms * 1e-3) / 1e12, 2),
                      "time_over_density_x_dense": round(s_ms / (eff * dense_ms), 3)}
