@@ -308,9 +308,13 @@ def main():
         qk_sets = [(dq, dk)] + [(dq.clone(), dk.clone()) for _ in range(n_sets - 1)]
         turn = [0]
         levels = []
+        bq, bk, _ = w.qkv_block_structured()
+        bq, bk = dev(bq), dev(bk)
         for action in (1, 2, 3):
             tau = ra.rapid_mask_level_tau(action)
             sel_call = lambda: ra.rapid_mask_select(dq, dk, sel_mask, w.block, w.kv_len, text_start, tau, 0.0, sel_ws)
+            ra.rapid_mask_select(bq, bk, sel_mask, w.block, w.kv_len, text_start, tau, 0.0, sel_ws)
+            kept_structured = round(float(sel_mask.float().mean()), 4)
 
             def sel_rotating():
                 i = turn[0] = (turn[0] + 1) % n_sets
@@ -320,7 +324,8 @@ def main():
             levels.append({"action": action, "tau": round(tau, 3),
                            "ms": round(time_graph(sel_rotating, 4 * n_sets), 5),
                            "ms_inputs_in_memory_side_cache": round(time_graph(sel_call, 20), 5),
-                           "kept_fraction_on_this_input": round(float(sel_mask.float().mean()), 4)})
+                           "kept_fraction_iid_inputs": round(float(sel_mask.float().mean()), 4),
+                           "kept_fraction_block_structured_inputs": kept_structured})
         gbs = read_bytes / (levels[0]["ms"] * 1e-3) / 1e9
         gbs_c = read_bytes / (levels[0]["ms_inputs_in_memory_side_cache"] * 1e-3) / 1e9
         out["mask_select"] = {"levels": levels, "qk_sets_rotated": n_sets,
@@ -328,11 +333,14 @@ def main():
                                            "achieved": round(gbs, 1), "peak": 8000.0, "unit": "GB/s",
                                            "frac": round(gbs / 8000.0, 4), "algorithmic_bytes": read_bytes,
                                            "achieved_inputs_in_memory_side_cache": round(gbs_c, 1)}}
-        del qk_sets
+        del qk_sets, bq, bk
 
     # ---- a scripted action trace of one image (counts as in the paper's appendix: 12-16 steps, 4-8 of
     # them reuse the cache, 2-4 run sparse attention) played against the library: the attention side
-    # of every layer of every computing step, the residual operations, mask selection on the GPU
+    # of every layer of every computing step, the residual operations, mask selection on the GPU.
+    # Twice: on Q, K with a block-structured attention map (the kind of map the selection is for; the
+    # sparse steps then prune) and on the i.i.d. tensors of the headline leg (nearly uniform pooled
+    # scores: nothing to prune, so a "sparse" step only adds the selection and the plan).
     if not args.no_trace and w.N % w.block == 0 and w.N // w.block <= 2048:
         from paper_2509_22323_amd.sampler import run_action_trace
         n_layers, base_steps = (57, 28) if w.D == 128 else (24, 28)    # FLUX.1 / SD3-medium attention layers
@@ -340,42 +348,44 @@ def main():
         lat = torch.randn(w.B, 4096 * 64, device="cuda").bfloat16()
         dl, oo = torch.zeros_like(lat), torch.randn(w.B, 4096 * 64, device="cuda").bfloat16()
         text_start = w.N - 512 if w.N > 1024 else w.N
-        run_action_trace(trace[:3], dq, dk, dv, do, 2, w.block, w.kv_len, text_start, lat, dl, oo)   # warm
-        tr = run_action_trace(trace, dq, dk, dv, do, n_layers, w.block, w.kv_len, text_start, lat, dl, oo)
-        # the same trace with the workload's own masks for the three levels (synthetic i.i.d. inputs
-        # give near-uniform pooled scores, so the masks selected on the GPU keep almost every block)
-        dens = [d for d in w.densities if isinstance(d, float) and d < 1.0]
-        given = None
-        if dens:
-            lv = [max(dens), max(dens), min(dens)]
-            given_masks = {a + 1: torch.from_numpy(w.mask(lv[a])).cuda() for a in range(3)}
-            given = run_action_trace(trace, dq, dk, dv, do, n_layers, w.block, w.kv_len, text_start, lat, dl, oo,
-                                     masks=given_masks)
-        kinds = [s_["kind"] for s_ in tr.steps]
-        mean_ms = lambda pred: float(np.mean([s_["ms"] for s_ in tr.steps if pred(s_["kind"])] or [float("nan")]))
-        full_ms = mean_ms(lambda kd: kd == "full")
+        sq, sk, sv = (dev(x) for x in w.qkv_block_structured())
+        base_ms = base_steps * n_layers * ev_mean
+
+        def play(tq, tk, tv):
+            run_action_trace(trace[:3], tq, tk, tv, do, 2, w.block, w.kv_len, text_start, lat, dl, oo)   # warm
+            ramp(dense_call, args.leg_ramp_ms)
+            tr = run_action_trace(trace, tq, tk, tv, do, n_layers, w.block, w.kv_len, text_start, lat, dl, oo)
+            kinds = [s_["kind"] for s_ in tr.steps]
+            mean_ms = lambda pred: float(np.mean([s_["ms"] for s_ in tr.steps if pred(s_["kind"])] or [float("nan")]))
+            full_ms = mean_ms(lambda kd: kd == "full")
+            sparse_ms = mean_ms(lambda kd: kd.startswith("sparse"))
+            kept = {}
+            sel_mask = torch.empty(w.B, w.H, w.N // w.block, w.N // w.block, dtype=torch.uint8, device="cuda")
+            for action in (1, 2, 3):
+                ra.rapid_mask_select(tq, tk, sel_mask, w.block, w.kv_len, text_start, ra.rapid_mask_level_tau(action))
+                kept[f"level_{action}"] = round(float(sel_mask.float().mean()), 4)
+            return tr, kinds, {
+                "attention_ms": round(tr.total_ms, 3), "full_step_ms": round(full_ms, 3),
+                "sparse_step_ms": round(sparse_ms, 3), "cached_step_ms": round(mean_ms(lambda kd: kd == "cached"), 4),
+                "attention_time_ratio_vs_base_schedule": round(base_ms / tr.total_ms, 3),
+                "measured_sparse_step_cost_reduction": round(1.0 - sparse_ms / full_ms, 3),
+                "equivalent_steps_measured_attention": round(tr.total_ms / full_ms, 3),
+                "kept_fraction_of_selected_masks": kept}
+
+        tr, kinds, structured = play(sq, sk, sv)
+        _, _, iid = play(dq, dk, dv)
         cc = [0.95 if kd == "cached" else 0.0 for kd in kinds]
         cs = [{"sparse-1": 0.05, "sparse-2": 0.07, "sparse-3": 0.10}.get(kd, 0.0) for kd in kinds]
         k_exact, k_round = ra.rapid_equivalent_steps(cc, cs)
-        base_ms = base_steps * n_layers * ev_mean
         out["sampler_trace"] = {
             "layers": n_layers, "steps": len(trace), "cached_steps": kinds.count("cached"),
             "sparse_steps": sum(kd.startswith("sparse") for kd in kinds),
-            "attention_ms": round(tr.total_ms, 3), "full_step_ms": round(full_ms, 3),
-            "sparse_step_ms": round(mean_ms(lambda kd: kd.startswith("sparse")), 3),
-            "cached_step_ms": round(mean_ms(lambda kd: kd == "cached"), 4),
             "base_schedule": f"{base_steps} dense steps", "base_schedule_ms": round(base_ms, 3),
-            "attention_time_ratio": round(base_ms / tr.total_ms, 3),
             "equivalent_steps_paper_constants": {"K_exact": round(k_exact, 3), "K": k_round},
-            "equivalent_steps_measured_attention": round(tr.total_ms / full_ms, 3),
-            "note": "masks selected on the GPU per layer; synthetic i.i.d. inputs give near-uniform pooled "
-                    "scores, so they keep 0.94-1.0 of the blocks here; quality is not measured (no generator)"}
-        if given is not None:
-            g_sparse = float(np.mean([s_["ms"] for s_ in given.steps if s_["kind"].startswith("sparse")]))
-            out["sampler_trace"]["with_given_masks"] = {
-                "nominal_density_of_levels_1_2_3": lv, "attention_ms": round(given.total_ms, 3),
-                "sparse_step_ms": round(g_sparse, 3), "attention_time_ratio": round(base_ms / given.total_ms, 3),
-                "measured_sparse_step_cost_reduction": round(1.0 - g_sparse / full_ms, 3)}
+            "block_structured_inputs": structured, "iid_inputs": iid,
+            "note": "masks selected on the GPU per layer; the same Q, K, V stand in for every layer; quality "
+                    "is not measured (no generator)"}
+        del sq, sk, sv
 
     # ---- Cache-Reuse residual operations (O = X + Delta, Delta = G(X) - X): streaming kernels,
     # bound by HBM (6 bytes per element).  Two sizes: the latent of one image at this workload's

@@ -66,6 +66,36 @@ RAPID_API int rapid_mask_select(const void* q, const void* k, int B, int H, int 
 RAPID_API size_t rapid_mask_select_workspace_bytes(int B, int H, int N, int D, int block);
 
 /*
+ * The same selection on Q and K as an MM-DiT block holds them (Sec. 3.1: image and text
+ * stream are separate tensors, joined only for attention), so that the mask for
+ * rapid_attn_joint comes from the very tensors that call reads, without a concatenated
+ * copy.  Same rule, same kernels.
+ *   segments     HOST array of n_segments (1 or 2) rapid_attn_segment descriptors, read
+ *                during the call: q, k, n and in_stride_* are used, v and o are ignored
+ *                (may be NULL).  Constraints as for rapid_attn_joint: pointers 16-byte
+ *                aligned, strides multiples of 8 elements, D <= in_stride_n <= 2^23; with
+ *                two segments segments[0].n is a multiple of 128 and in_stride_h,
+ *                in_stride_n are the same in both.  N = sum of the n.
+ *   block        64 or 128; nb = ceil(N/block) <= 2048, the last block ends at N
+ *   kv_len       valid tokens of every sample, 1..N; 0 selects N
+ *   kv_lens      device, int32 [B], or NULL: per-sample valid tokens, each clamped to 0..N;
+ *                replaces kv_len when given.  Live blocks, block means and the text blocks
+ *                (text_start < that sample's length) are taken per sample; a sample with
+ *                0 valid tokens gets an all-zero mask.
+ *   mask         device, uint8 [B,H,nb,nb]
+ *   workspace    at least rapid_mask_select_joint_workspace_bytes(B,H,N,D,block) bytes
+ *   other arguments, semantics and errors as rapid_mask_select.
+ */
+RAPID_API int rapid_mask_select_joint(const rapid_attn_segment* segments, int n_segments,
+                                      int B, int H, int D, int block, int kv_len, const int* kv_lens,
+                                      int text_start, float tau, float scale,
+                                      unsigned char* mask, void* workspace, size_t workspace_bytes,
+                                      void* stream);
+
+/* Workspace bytes of rapid_mask_select_joint (N = total tokens, any positive count). */
+RAPID_API size_t rapid_mask_select_joint_workspace_bytes(int B, int H, int N, int D, int block);
+
+/*
  * The library's default tau for a Sparse-Attention action (Sec. 3.3 (c)): action 0
  * (full attention) -> 1.0, actions 1, 2, 3 -> 0.98, 0.95, 0.90 (progressively
  * sparser; values of this library, not of the paper); anything else -> NaN.

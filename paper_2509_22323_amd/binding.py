@@ -31,7 +31,8 @@ class Segment(ctypes.Structure):
                 ("in_stride_b", ctypes.c_longlong), ("in_stride_h", ctypes.c_longlong), ("in_stride_n", ctypes.c_longlong),
                 ("out_stride_b", ctypes.c_longlong), ("out_stride_h", ctypes.c_longlong),
                 ("out_stride_n", ctypes.c_longlong)]
-MASK_EXPORTS = ("rapid_mask_select", "rapid_mask_select_workspace_bytes", "rapid_mask_level_tau")
+MASK_EXPORTS = ("rapid_mask_select", "rapid_mask_select_workspace_bytes", "rapid_mask_select_joint",
+                "rapid_mask_select_joint_workspace_bytes", "rapid_mask_level_tau")
 CACHE_EXPORTS = ("rapid_cache_store", "rapid_cache_reuse", "rapid_equivalent_steps", "rapid_reward")
 
 
@@ -87,6 +88,10 @@ def library():
     lib.rapid_mask_select.restype = ci
     lib.rapid_mask_select_workspace_bytes.argtypes = [ci, ci, ci, ci, ci]
     lib.rapid_mask_select_workspace_bytes.restype = sz
+    lib.rapid_mask_select_joint.argtypes = [ctypes.POINTER(Segment), ci, ci, ci, ci, ci, ci, vp, ci, cf, cf, vp, vp, sz, vp]
+    lib.rapid_mask_select_joint.restype = ci
+    lib.rapid_mask_select_joint_workspace_bytes.argtypes = [ci, ci, ci, ci, ci]
+    lib.rapid_mask_select_joint_workspace_bytes.restype = sz
     lib.rapid_mask_level_tau.argtypes = [ci]
     lib.rapid_mask_level_tau.restype = cf
     cd, dp = ctypes.c_double, ctypes.POINTER(ctypes.c_double)
@@ -332,4 +337,61 @@ def rapid_mask_select(q, k, mask, block, kv_len=None, text_start=None, tau=0.95,
     _check(library().rapid_mask_select(q.data_ptr(), k.data_ptr(), B, H, N, D, int(block), kv_len, text_start,
                                        float(tau), float(scale), mask.data_ptr(), workspace.data_ptr(),
                                        workspace.numel() * workspace.element_size(), _stream(q)))
+    return mask
+
+
+def rapid_mask_select_joint_workspace_bytes(B: int, H: int, N: int, D: int, block: int) -> int:
+    return int(library().rapid_mask_select_joint_workspace_bytes(B, H, N, D, block))
+
+
+def rapid_mask_select_joint(segments, mask, block, kv_len=None, kv_lens=None, text_start=None, tau=0.95, scale=0.0,
+                            workspace=None):
+    """rapid_mask_select on Q and K given as one or two token segments: `segments` is a sequence of
+    (q, k) pairs (tuples as passed to rapid_attn_joint work too: only their first two tensors are
+    used), each a CUDA bf16 tensor indexed [B, H, n, D] with a contiguous last dimension; q and k of
+    a segment share their strides.  mask: CUDA uint8 [B, H, nb, nb], nb = ceil(N / block)."""
+    import torch
+    if len(segments) not in (1, 2):
+        raise ValueError("one or two segments")
+    descr = (Segment * len(segments))()
+    B = H = D = None
+    N = 0
+    for i, seg in enumerate(segments):
+        q, k = seg[0], seg[1]
+        for name, t in (("q", q), ("k", k)):
+            if not (isinstance(t, torch.Tensor) and t.is_cuda and t.dtype == torch.bfloat16 and t.dim() == 4
+                    and t.stride(3) == 1):
+                raise TypeError(f"segment {i}: {name} must be a CUDA bfloat16 tensor [B,H,n,D] with contiguous D")
+            if t.shape != q.shape or t.device != q.device:
+                raise ValueError(f"segment {i}: {name} shape/device differs from q")
+        if k.stride() != q.stride():
+            raise ValueError(f"segment {i}: q and k must share their strides")
+        if B is None:
+            B, H, _, D = (int(x) for x in q.shape)
+        elif (int(q.shape[0]), int(q.shape[1]), int(q.shape[3])) != (B, H, D):
+            raise ValueError("segments differ in B, H or D")
+        g = descr[i]
+        g.q, g.k, g.v, g.o, g.n = q.data_ptr(), k.data_ptr(), None, None, int(q.shape[2])
+        g.in_stride_b, g.in_stride_h, g.in_stride_n = q.stride(0), q.stride(1), q.stride(2)
+        N += int(q.shape[2])
+    q0 = segments[0][0]
+    nb = -(-N // int(block)) if block > 0 else 0
+    if not (isinstance(mask, torch.Tensor) and mask.is_cuda and mask.dtype == torch.uint8 and mask.is_contiguous()
+            and mask.device == q0.device):
+        raise TypeError("mask must be a contiguous CUDA uint8 tensor")
+    if tuple(mask.shape) != (B, H, nb, nb):
+        raise ValueError(f"mask shape {tuple(mask.shape)} != {(B, H, nb, nb)}")
+    lens_ptr = None
+    if kv_lens is not None:
+        if not (isinstance(kv_lens, torch.Tensor) and kv_lens.is_cuda and kv_lens.dtype == torch.int32
+                and kv_lens.is_contiguous() and kv_lens.numel() == B and kv_lens.device == q0.device):
+            raise TypeError("kv_lens must be a contiguous CUDA int32 tensor [B]")
+        lens_ptr = kv_lens.data_ptr()
+    if workspace is None:
+        workspace = torch.empty(max(rapid_mask_select_joint_workspace_bytes(B, H, N, D, int(block)), 16),
+                                dtype=torch.uint8, device=q0.device)
+    _check(library().rapid_mask_select_joint(
+        descr, len(segments), B, H, D, int(block), 0 if kv_len is None else int(kv_len), lens_ptr,
+        N if text_start is None else int(text_start), float(tau), float(scale), mask.data_ptr(),
+        workspace.data_ptr(), workspace.numel() * workspace.element_size(), _stream(q0)))
     return mask

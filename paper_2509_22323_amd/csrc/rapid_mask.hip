@@ -20,31 +20,60 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int MAX_NB = 2048;      // mask blocks per side the selection kernel holds in LDS
 
+// Q and K of the joint sequence as one or two token segments (the image and the text stream of
+// an MM-DiT block): token t < n0 is row t of segment 0, any other token row t - n0 of segment 1.
+// Strides in elements, D contiguous; head and token strides are common to both segments.
+struct QKView {
+    const uint16_t* q0; const uint16_t* k0;
+    const uint16_t* q1; const uint16_t* k1;      // null when there is one segment
+    long long sb0, sb1, sh, sn;
+    int n0, N, H;
+    int kv_len;                                   // valid tokens of every sample, or
+    const int32_t* kv_lens;                       // per sample (device, [B]), clamped to 0..N
+    int text_start;
+};
+
+__device__ __forceinline__ int valid_tokens(const QKView& v, int b)
+{
+    if (v.kv_lens == nullptr) return v.kv_len;
+    const int n = v.kv_lens[b];
+    return n < 0 ? 0 : (n > v.N ? v.N : n);
+}
+// live blocks (those that start below the valid length) and the first text block of a sample
+__device__ __forceinline__ void sample_blocks(const QKView& v, int b, int block, int nb, int& live, int& first_text)
+{
+    const int kv = valid_tokens(v, b);
+    live = (kv + block - 1) / block;
+    first_text = v.text_start < kv ? v.text_start / block : nb;
+}
+
 // means[(which, bh, i), :] = mean over the valid rows of block i of Q (which = 0) or K (1).
 // 256 threads: D/8 column groups of 8 elements x 256/(D/8) row groups; every thread adds up
 // its rows in increasing order, the row groups are then added in increasing order.
 template <int D>
-__global__ __launch_bounds__(256) void block_mean_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
-                                                         int N, int block, int kv_len, int nb, float* __restrict__ means,
+__global__ __launch_bounds__(256) void block_mean_kernel(const QKView v, int block, int nb, float* __restrict__ means,
                                                          size_t which_stride)
 {
     constexpr int CG = D / 8, RG = 256 / CG;
     __shared__ float red[RG][D];
     const int i = blockIdx.x % nb, bh = blockIdx.x / nb, which = blockIdx.y;
-    const uint16_t* src = (which ? k : q) + (size_t)bh * N * D;
+    const int b = bh / v.H, h = bh % v.H;
+    const uint16_t* s0 = (which ? v.k0 : v.q0) + (size_t)b * v.sb0 + (size_t)h * v.sh;
+    const uint16_t* s1 = v.q1 ? (which ? v.k1 : v.q1) + (size_t)b * v.sb1 + (size_t)h * v.sh - (size_t)v.n0 * v.sn : s0;
+    const int kv = valid_tokens(v, b);
     const int lo = i * block;
     int hi = lo + block;
-    hi = hi < kv_len ? hi : kv_len;
+    hi = hi < kv ? hi : kv;                        // kv <= N: a ragged last block ends at N
     const int c = threadIdx.x % CG, g = threadIdx.x / CG;
     float acc[8];
 #pragma unroll
     for (int e = 0; e < 8; ++e) acc[e] = 0.f;
     for (int r = lo + g; r < hi; r += RG) {
-        const u32x4 v = *(const u32x4*)(src + (size_t)r * D + c * 8);
+        const u32x4 x = *(const u32x4*)((r < v.n0 ? s0 : s1) + (size_t)r * v.sn + c * 8);
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-            acc[2 * e] += __uint_as_float(v[e] << 16);
-            acc[2 * e + 1] += __uint_as_float(v[e] & 0xffff0000u);
+            acc[2 * e] += __uint_as_float(x[e] << 16);
+            acc[2 * e + 1] += __uint_as_float(x[e] & 0xffff0000u);
         }
     }
 #pragma unroll
@@ -74,7 +103,7 @@ __device__ __forceinline__ float wave_sum(float v)
 // One wavefront per mask row (b, h, i); four rows per workgroup.
 template <int D>
 __global__ __launch_bounds__(256) void select_blocks_kernel(const float* __restrict__ qmean, const float* __restrict__ kmean,
-                                                            int rows, int nb, int live, int first_text, float tau,
+                                                            const QKView v, int block, int rows, int nb, float tau,
                                                             float scale, unsigned char* __restrict__ mask)
 {
     __shared__ float qrow[4][D];
@@ -84,6 +113,8 @@ __global__ __launch_bounds__(256) void select_blocks_kernel(const float* __restr
     if (row >= rows) return;
     const int i = row % nb;
     const size_t bh = row / nb;
+    int live, first_text;
+    sample_blocks(v, (int)(bh / v.H), block, nb, live, first_text);
     unsigned char* out = mask + (size_t)row * nb;
     if (i >= live) {
         for (int j = lane; j < nb; j += 64) out[j] = 0;
@@ -160,8 +191,8 @@ constexpr int SMALL_ROWS = 4 * SMALL_RPW;     // per workgroup
 
 template <int D>
 __global__ __launch_bounds__(256) void select_blocks_small_kernel(const float* __restrict__ qmean,
-                                                                  const float* __restrict__ kmean, int nb, int live,
-                                                                  int first_text, float tau, float scale,
+                                                                  const float* __restrict__ kmean, const QKView v,
+                                                                  int block, int nb, float tau, float scale,
                                                                   unsigned char* __restrict__ mask)
 {
     constexpr int KROW = D + 4;
@@ -170,6 +201,8 @@ __global__ __launch_bounds__(256) void select_blocks_small_kernel(const float* _
     __shared__ float ps[SMALL_ROWS][SMALL_NB];
     const int groups = (nb + SMALL_ROWS - 1) / SMALL_ROWS;
     const size_t bh = blockIdx.x / groups;
+    int live, first_text;
+    sample_blocks(v, (int)(bh / v.H), block, nb, live, first_text);
     const int i0 = (blockIdx.x % groups) * SMALL_ROWS;
     const int tid = threadIdx.x, wv = tid >> 6, lane = tid & 63;
 
@@ -263,14 +296,56 @@ inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 
 
 size_t means_bytes(int B, int H, int nb, int D) { return (size_t)2 * B * H * nb * D * sizeof(float); }
 
-bool shape_ok(int B, int H, int N, int D, int block)
+bool shape_ok(int B, int H, int N, int D, int block, bool ragged)
 {
     if (B <= 0 || H <= 0 || N <= 0 || N > (1 << 22)) return false;
     if ((long long)B * H > 0x7fffffffLL / 4096) return false;
     if (D != 64 && D != 128) return false;
     if (block != 64 && block != 128) return false;
-    if (N % block != 0 || N / block > MAX_NB) return false;
+    if (!ragged && N % block != 0) return false;
+    if ((N + block - 1) / block > MAX_NB) return false;
     return true;
+}
+
+// One validated call: means, then the selection kernel that fits the size.
+int run_select(const QKView& v, int B, int D, int block, float tau, float scale, unsigned char* mask, void* workspace,
+               size_t workspace_bytes, void* stream)
+{
+    const int H = v.H, nb = (v.N + block - 1) / block;
+    if (nb > MAX_NB) return RAPID_ERR_UNSUPPORTED;
+    const size_t need = means_bytes(B, H, nb, D);
+    if (!workspace || workspace_bytes < need) return RAPID_ERR_WORKSPACE;
+    if (!aligned16(workspace)) return RAPID_ERR_ALIGN;
+    if ((long long)B * H * nb > 0x7fffffffLL / 16) return RAPID_ERR_SHAPE;
+    if (!(scale > 0.f)) scale = 1.0f / sqrtf((float)D);
+
+    float* means = (float*)workspace;
+    const size_t which_stride = (size_t)B * H * nb * D;
+    hipStream_t s = (hipStream_t)stream;
+    const dim3 g1((unsigned)(nb * B * H), 2u);
+    if (D == 64) hipLaunchKernelGGL((block_mean_kernel<64>), g1, dim3(256), 0, s, v, block, nb, means, which_stride);
+    else hipLaunchKernelGGL((block_mean_kernel<128>), g1, dim3(256), 0, s, v, block, nb, means, which_stride);
+    if (hipGetLastError() != hipSuccess) return RAPID_ERR_DEVICE;
+
+    const int rows = B * H * nb;
+    if (nb <= SMALL_NB) {
+        const dim3 gs((unsigned)(B * H * ((nb + SMALL_ROWS - 1) / SMALL_ROWS)));
+        if (D == 64)
+            hipLaunchKernelGGL((select_blocks_small_kernel<64>), gs, dim3(256), 0, s, means, means + which_stride, v, block,
+                               nb, tau, scale, mask);
+        else
+            hipLaunchKernelGGL((select_blocks_small_kernel<128>), gs, dim3(256), 0, s, means, means + which_stride, v, block,
+                               nb, tau, scale, mask);
+        return hipGetLastError() == hipSuccess ? RAPID_OK : RAPID_ERR_DEVICE;
+    }
+    const dim3 g2((unsigned)((rows + 3) / 4));
+    if (D == 64)
+        hipLaunchKernelGGL((select_blocks_kernel<64>), g2, dim3(256), 0, s, means, means + which_stride, v, block, rows, nb,
+                           tau, scale, mask);
+    else
+        hipLaunchKernelGGL((select_blocks_kernel<128>), g2, dim3(256), 0, s, means, means + which_stride, v, block, rows, nb,
+                           tau, scale, mask);
+    return hipGetLastError() == hipSuccess ? RAPID_OK : RAPID_ERR_DEVICE;
 }
 
 }  // namespace
@@ -288,54 +363,71 @@ int rapid_mask_select(const void* q, const void* k, int B, int H, int N, int D, 
     if (D != 64 && D != 128) return RAPID_ERR_UNSUPPORTED;
     if (block != 64 && block != 128) return RAPID_ERR_UNSUPPORTED;
     if (N % block != 0) return RAPID_ERR_SHAPE;
-    const int nb = N / block;
-    if (nb > MAX_NB) return RAPID_ERR_UNSUPPORTED;
+    if (N / block > MAX_NB) return RAPID_ERR_UNSUPPORTED;
     if (!aligned16(q) || !aligned16(k)) return RAPID_ERR_ALIGN;
-    const size_t need = means_bytes(B, H, nb, D);
-    if (!workspace || workspace_bytes < need) return RAPID_ERR_WORKSPACE;
-    if (!aligned16(workspace)) return RAPID_ERR_ALIGN;
-    if (!(scale > 0.f)) scale = 1.0f / sqrtf((float)D);
+    QKView v{};
+    v.q0 = (const uint16_t*)q; v.k0 = (const uint16_t*)k; v.q1 = nullptr; v.k1 = nullptr;
+    v.sb0 = (long long)H * N * D; v.sb1 = 0; v.sh = (long long)N * D; v.sn = D;
+    v.n0 = N; v.N = N; v.H = H;
+    v.kv_len = kv_len; v.kv_lens = nullptr; v.text_start = text_start;
+    return run_select(v, B, D, block, tau, scale, mask, workspace, workspace_bytes, stream);
+}
 
-    float* means = (float*)workspace;
-    const size_t which_stride = (size_t)B * H * nb * D;
-    hipStream_t s = (hipStream_t)stream;
-    if ((long long)B * H * nb > 0x7fffffffLL / 16) return RAPID_ERR_SHAPE;
-    const dim3 g1((unsigned)(nb * B * H), 2u);
-    if (D == 64)
-        hipLaunchKernelGGL((block_mean_kernel<64>), g1, dim3(256), 0, s, (const uint16_t*)q, (const uint16_t*)k, N, block,
-                           kv_len, nb, means, which_stride);
-    else
-        hipLaunchKernelGGL((block_mean_kernel<128>), g1, dim3(256), 0, s, (const uint16_t*)q, (const uint16_t*)k, N, block,
-                           kv_len, nb, means, which_stride);
-    if (hipGetLastError() != hipSuccess) return RAPID_ERR_DEVICE;
-
-    const int rows = B * H * nb;
-    const int live = (kv_len + block - 1) / block;
-    const int first_text = text_start < kv_len ? text_start / block : nb;
-    if (nb <= SMALL_NB) {
-        const dim3 gs((unsigned)(B * H * ((nb + SMALL_ROWS - 1) / SMALL_ROWS)));
-        if (D == 64)
-            hipLaunchKernelGGL((select_blocks_small_kernel<64>), gs, dim3(256), 0, s, means, means + which_stride, nb, live,
-                               first_text, tau, scale, mask);
-        else
-            hipLaunchKernelGGL((select_blocks_small_kernel<128>), gs, dim3(256), 0, s, means, means + which_stride, nb, live,
-                               first_text, tau, scale, mask);
-        return hipGetLastError() == hipSuccess ? RAPID_OK : RAPID_ERR_DEVICE;
+int rapid_mask_select_joint(const rapid_attn_segment* segments, int n_segments, int B, int H, int D, int block,
+                            int kv_len, const int* kv_lens, int text_start, float tau, float scale,
+                            unsigned char* mask, void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (!segments || !mask) return RAPID_ERR_NULL;
+    if (n_segments != 1 && n_segments != 2) return RAPID_ERR_SHAPE;
+    if (B <= 0 || H <= 0) return RAPID_ERR_SHAPE;
+    if ((long long)B * H > 0x7fffffffLL / 4096) return RAPID_ERR_SHAPE;
+    if (D != 64 && D != 128) return RAPID_ERR_UNSUPPORTED;
+    if (block != 64 && block != 128) return RAPID_ERR_UNSUPPORTED;
+    if (text_start < 0 || !(tau > 0.f)) return RAPID_ERR_SHAPE;
+    long long N = 0;
+    for (int i = 0; i < n_segments; ++i) {
+        const rapid_attn_segment& g = segments[i];
+        if (!g.q || !g.k) return RAPID_ERR_NULL;               // v and o are not read
+        if (g.n <= 0) return RAPID_ERR_SHAPE;
+        if (!aligned16(g.q) || !aligned16(g.k)) return RAPID_ERR_ALIGN;
+        const long long st[3] = {g.in_stride_b, g.in_stride_h, g.in_stride_n};
+        for (int j = 0; j < 3; ++j) {
+            if (st[j] < 0 || st[j] > (1LL << 40)) return RAPID_ERR_SHAPE;
+            if (st[j] % 8 != 0) return RAPID_ERR_ALIGN;        // every row starts on 16 bytes
+        }
+        if (g.in_stride_n < D || g.in_stride_n > (1LL << 23)) return RAPID_ERR_SHAPE;
+        N += g.n;
     }
-    const dim3 g2((unsigned)((rows + 3) / 4));
-    if (D == 64)
-        hipLaunchKernelGGL((select_blocks_kernel<64>), g2, dim3(256), 0, s, means, means + which_stride, rows, nb, live,
-                           first_text, tau, scale, mask);
-    else
-        hipLaunchKernelGGL((select_blocks_kernel<128>), g2, dim3(256), 0, s, means, means + which_stride, rows, nb, live,
-                           first_text, tau, scale, mask);
-    return hipGetLastError() == hipSuccess ? RAPID_OK : RAPID_ERR_DEVICE;
+    if (N > (1 << 22)) return RAPID_ERR_SHAPE;
+    if (n_segments == 2) {
+        // as rapid_attn_joint: the masks made here are for that call
+        if (segments[0].n % 128 != 0) return RAPID_ERR_SHAPE;
+        if (segments[0].in_stride_h != segments[1].in_stride_h || segments[0].in_stride_n != segments[1].in_stride_n)
+            return RAPID_ERR_SHAPE;
+    }
+    if (kv_len == 0) kv_len = (int)N;
+    if (kv_len < 1 || kv_len > N) return RAPID_ERR_SHAPE;
+    QKView v{};
+    v.q0 = (const uint16_t*)segments[0].q; v.k0 = (const uint16_t*)segments[0].k;
+    v.q1 = n_segments == 2 ? (const uint16_t*)segments[1].q : nullptr;
+    v.k1 = n_segments == 2 ? (const uint16_t*)segments[1].k : nullptr;
+    v.sb0 = segments[0].in_stride_b; v.sb1 = n_segments == 2 ? segments[1].in_stride_b : 0;
+    v.sh = segments[0].in_stride_h; v.sn = segments[0].in_stride_n;
+    v.n0 = n_segments == 2 ? segments[0].n : (int)N; v.N = (int)N; v.H = H;
+    v.kv_len = kv_len; v.kv_lens = kv_lens; v.text_start = text_start;
+    return run_select(v, B, D, block, tau, scale, mask, workspace, workspace_bytes, stream);
 }
 
 size_t rapid_mask_select_workspace_bytes(int B, int H, int N, int D, int block)
 {
-    if (!shape_ok(B, H, N, D, block)) return 0;
+    if (!shape_ok(B, H, N, D, block, false)) return 0;
     return means_bytes(B, H, N / block, D);
+}
+
+size_t rapid_mask_select_joint_workspace_bytes(int B, int H, int N, int D, int block)
+{
+    if (!shape_ok(B, H, N, D, block, true)) return 0;
+    return means_bytes(B, H, (N + block - 1) / block, D);
 }
 
 float rapid_mask_level_tau(int action)

@@ -76,14 +76,9 @@ def test_levels_are_nested_and_tau_one_is_dense():
 
 
 def test_custom_scale_and_block_structured_inputs():
-    rng = np.random.default_rng(4)
     B, H, nb, block, D = 1, 2, 16, 128, 128
     N = nb * block
-    centers_k = rng.normal(size=(H, nb, D)) * 1.5
-    centers_q = centers_k[:, rng.permutation(nb)] + rng.normal(size=(H, nb, D)) * 0.3
-    q = np.repeat(centers_q, block, axis=1)[None] + rng.normal(size=(B, H, N, D)) * 0.2
-    k = np.repeat(centers_k, block, axis=1)[None] + rng.normal(size=(B, H, N, D)) * 0.2
-    qb, kb = wl.f32_to_bf16_bits(q.astype(np.float32)), wl.f32_to_bf16_bits(k.astype(np.float32))
+    qb, kb, _ = wl.make_qkv_block_structured(B, H, N, D, block, seed=4)
     got = check(qb, kb, block, N, N + 1, 0.9)
     assert got.mean() < 0.5
     check(qb, kb, block, N, N + 1, 0.9, scale=0.03)
@@ -103,3 +98,82 @@ def test_selected_mask_feeds_the_sparse_attention():
     ra.rapid_attn_block_sparse(dq, dk, dv, o, m, block, kv_len)
     torch.cuda.synchronize()
     assert_close(from_dev(o), oracle.attention(q, k, v, kv_len, m.cpu().numpy(), block), "select + sparse")
+
+
+# ---------------------------------------------------------------- the model-shaped form
+def oracle_joint_mask(q, k, block, kv_lens, text_start, tau):
+    """Per sample (each has its own valid length), on the contiguous data padded to whole blocks
+    with NaN rows (beyond every valid length, so the oracle must ignore them)."""
+    B, H, N, D = q.shape
+    nb = -(-N // block)
+    pad = lambda x: np.concatenate([x, np.full((B, H, nb * block - N, D), wl.BF16_NAN, np.uint16)], axis=2)
+    qp, kp = pad(q), pad(k)
+    out = np.zeros((B, H, nb, nb), np.uint8)
+    for b in range(B):
+        if kv_lens[b] > 0:
+            out[b] = mo.select_mask(qp[b:b + 1], kp[b:b + 1], block, int(kv_lens[b]), text_start, tau)[0]
+    return out
+
+
+JOINT = [
+    # B, H, n_img, n_txt, D, block, lens (None = all tokens), fused
+    (2, 3, 512, 77, 64, 128, None, False),
+    (3, 2, 640, 100, 128, 128, (740, 0, 655), True),       # per-sample lengths, one sample empty
+    (2, 2, 256, 64, 128, 64, (300, 320), True),
+    (1, 2, 333, 0, 64, 64, (301,), False),                 # one ragged token-major segment
+    (1, 2, 4096, 333, 64, 128, None, True),                # the SD3-like joint shape, ragged last block
+]
+
+
+@pytest.mark.parametrize("B,H,n_img,n_txt,D,block,lens,fused", JOINT)
+@pytest.mark.parametrize("tau", [0.6, 0.95])
+def test_joint_selection_matches_the_oracle(B, H, n_img, n_txt, D, block, lens, fused, tau):
+    from test_gpu_joint import as_model_tensors
+    N = n_img + n_txt
+    nb = -(-N // block)
+    lens = np.array([N] * B if lens is None else lens, np.int32)
+    q, k, v = wl.make_qkv_block_structured(B, H, N, D, block, seed=N + D, n_text_blocks=-(-n_txt // block))
+    segs, _ = as_model_tensors(q, k, v, n_img, fused)
+    m = torch.full((B, H, nb, nb), 9, dtype=torch.uint8, device="cuda")
+    ra.rapid_mask_select_joint(segs, m, block, kv_lens=torch.from_numpy(lens).cuda(), text_start=n_img, tau=tau)
+    torch.cuda.synchronize()
+    got = m.cpu().numpy()
+    assert set(np.unique(got)) <= {0, 1}
+    lo, hi, mid = (oracle_joint_mask(q, k, block, lens, n_img, t) for t in (tau - DELTA, tau + DELTA, tau))
+    assert (lo <= got).all() and (got <= hi).all(), ((lo > got).sum(), (got > hi).sum())
+    assert (got == mid).mean() >= 0.999
+    live_img = min(n_img, int(lens.max())) // block
+    if live_img >= 4:
+        assert got[lens.argmax(), :, :live_img, :live_img].mean() < 0.9      # it prunes on these inputs
+    # the same bits as the contiguous entry point on a contiguous copy, where that one applies
+    if N % block == 0 and len(set(lens.tolist())) == 1 and lens[0] > 0:
+        m2 = torch.empty_like(m)
+        ra.rapid_mask_select(to_dev(q), to_dev(k), m2, block, int(lens[0]), n_img, tau)
+        torch.cuda.synchronize()
+        np.testing.assert_array_equal(got, m2.cpu().numpy())
+
+
+def test_joint_select_then_joint_attend_on_the_same_tensors():
+    """The composition the model needs: mask from the image and text tensors as they are, then
+    attention on the same tensors, per-sample lengths in both; against the oracle's attention
+    under the selected mask."""
+    import oracle
+    from gpu_common import assert_close
+    from test_gpu_joint import as_model_tensors, gather, oracle_joint
+    B, H, n_img, n_txt, D, block = 2, 3, 1024, 154, 128, 128
+    N = n_img + n_txt
+    nb = -(-N // block)
+    lens = np.array([N, N - 60], np.int32)
+    q, k, v = wl.make_qkv_block_structured(B, H, N, D, block, seed=77, n_text_blocks=2)
+    segs, guards = as_model_tensors(q, k, v, n_img, True)
+    dl = torch.from_numpy(lens).cuda()
+    m = torch.empty((B, H, nb, nb), dtype=torch.uint8, device="cuda")
+    ra.rapid_mask_select_joint(segs, m, block, kv_lens=dl, text_start=n_img, tau=0.9)
+    ra.rapid_attn_joint(segs, m, block, kv_lens=dl)
+    torch.cuda.synchronize()
+    mask = m.cpu().numpy()
+    assert 0.2 < mask.mean() < 0.9
+    got = gather(segs)
+    for b in range(B):
+        ref = oracle_joint(q[b:b + 1], k[b:b + 1], v[b:b + 1], int(lens[b]), mask[b:b + 1], block)
+        assert_close(got[b:b + 1], ref, f"sample {b}")

@@ -47,3 +47,37 @@ def test_default_levels_are_nested_and_match_the_oracle_table():
     assert taus[0] == 1.0 and taus == sorted(taus, reverse=True) and len(set(taus)) == 4
     assert all(abs(t - w) < 1e-7 for t, w in zip(taus, mo.LEVEL_TAU))
     assert math.isnan(ra.rapid_mask_level_tau(4)) and math.isnan(ra.rapid_mask_level_tau(-1))
+
+
+def seg(n=256, q=A, k=A + 0x100000, H=2, D=64, **over):
+    g = binding.Segment()
+    g.q, g.k, g.v, g.o, g.n = q, k, None, None, n
+    g.in_stride_b, g.in_stride_h, g.in_stride_n = n * H * D, D, H * D
+    for name, val in over.items():
+        setattr(g, name, val)
+    return g
+
+
+def joint(segs, B=1, H=2, D=64, block=128, kv_len=0, text_start=256, tau=0.9, mask=M, ws=WS, ws_bytes=1 << 30):
+    arr = (binding.Segment * max(len(segs), 1))(*segs)
+    return ra.library().rapid_mask_select_joint(arr if segs else None, len(segs), B, H, D, block, kv_len, None,
+                                                text_start, tau, 0.0, mask, ws, ws_bytes, None)
+
+
+def test_joint_selection_argument_errors_come_before_any_launch():
+    S = ra.STATUS
+    assert joint([]) == S["RAPID_ERR_NULL"] and joint([seg()], mask=None) == S["RAPID_ERR_NULL"]
+    assert joint([seg(q=None)]) == S["RAPID_ERR_NULL"] and joint([seg(k=None)]) == S["RAPID_ERR_NULL"]
+    assert joint([seg(), seg(), seg()]) == S["RAPID_ERR_SHAPE"]
+    assert joint([seg(n=0)]) == S["RAPID_ERR_SHAPE"] and joint([seg()], kv_len=257) == S["RAPID_ERR_SHAPE"]
+    assert joint([seg()], tau=0.0) == S["RAPID_ERR_SHAPE"] and joint([seg()], text_start=-1) == S["RAPID_ERR_SHAPE"]
+    assert joint([seg(n=200), seg(n=77)]) == S["RAPID_ERR_SHAPE"]             # first segment not a multiple of 128
+    assert joint([seg(n=256), seg(n=77, in_stride_n=3 * 2 * 64)]) == S["RAPID_ERR_SHAPE"]
+    assert joint([seg(in_stride_n=32)]) == S["RAPID_ERR_SHAPE"]
+    assert joint([seg(q=A + 8)]) == S["RAPID_ERR_ALIGN"] and joint([seg(in_stride_n=2 * 64 + 4)]) == S["RAPID_ERR_ALIGN"]
+    assert joint([seg()], D=96) == S["RAPID_ERR_UNSUPPORTED"] and joint([seg()], block=32) == S["RAPID_ERR_UNSUPPORTED"]
+    need = ra.rapid_mask_select_joint_workspace_bytes(1, 2, 333, 64, 128)
+    assert need == ra.rapid_mask_select_workspace_bytes(1, 2, 384, 64, 128) > 0
+    assert joint([seg(n=256), seg(n=77)], ws=None) == S["RAPID_ERR_WORKSPACE"]
+    assert joint([seg(n=256), seg(n=77)], ws_bytes=need - 1) == S["RAPID_ERR_WORKSPACE"]
+    assert ra.rapid_mask_select_joint_workspace_bytes(1, 2, 0, 64, 128) == 0

@@ -96,3 +96,21 @@ def test_sample_rows_cover_edges():
     assert rows.shape == (64, 3) and len({tuple(r) for r in rows}) == 64
     t = {tuple(r) for r in rows}
     assert (0, 0, 0) in t and (1, 2, 4428) in t and (0, 2, 4479) in t
+
+
+def test_block_structured_inputs_have_a_prunable_map():
+    """The generator for the mask-selection legs: seeded, padded like make_qkv, and (checked with
+    the selection oracle) its pooled attention map concentrates on few key-blocks per row, which
+    i.i.d. inputs of the same shape do not."""
+    from oracle import mask_oracle as mo
+    B, H, nb, block, D = 1, 2, 12, 64, 64
+    N = nb * block
+    a = wl.make_qkv_block_structured(B, H, N, D, block, kv_len=N - 10, seed=5, n_text_blocks=2, pad_fill="nan")
+    b = wl.make_qkv_block_structured(B, H, N, D, block, kv_len=N - 10, seed=5, n_text_blocks=2, pad_fill="nan")
+    for x, y in zip(a, b):
+        assert x.dtype == np.uint16 and x.shape == (B, H, N, D) and (x == y).all()
+        assert (x[:, :, N - 10:] == wl.BF16_NAN).all() and not (x[:, :, :N - 10] == wl.BF16_NAN).any()
+    structured = mo.select_mask(a[0], a[1], block, N - 10, N, 0.9)
+    plain_q, plain_k, _ = wl.make_qkv(B, H, N, D, N - 10, seed=5)
+    plain = mo.select_mask(plain_q, plain_k, block, N - 10, N, 0.9)
+    assert structured.mean() < 0.3 < 0.8 < plain.mean()

@@ -58,6 +58,41 @@ def make_qkv(B, H, N, D, kv_len=None, seed=BASE_SEED, gain=1.0, pad_fill="zero")
     return tuple(out)
 
 
+def make_qkv_block_structured(B, H, N, D, block, kv_len=None, seed=BASE_SEED, n_text_blocks=0,
+                              peak=5.5, link_noise=0.3, token_noise=0.2, pad_fill="zero"):
+    """Q, K, V (uint16 bf16 bits [B,H,N,D]) whose attention map has block structure, as the maps of
+    a trained DiT have and i.i.d. inputs have not: every key-block has a centre c_j ~ N(0, g^2),
+    every query-block looks at one key-block (a seeded permutation; the diagonal for text blocks)
+    with centre c_perm(i) + N(0, link_noise^2), tokens are their block's centre + N(0, token_noise^2).
+    g^2 = peak / sqrt(D), so that under the 1/sqrt(D) scale the linked block's score stands about
+    `peak` above the others whatever the head size (at 5.5: most of a row's mass, not all of it, so
+    that selection levels of different strictness keep different numbers of blocks).
+    V is i.i.d. N(0,1).  Only draws and the structure rule: no attention arithmetic."""
+    kv_len = N if kv_len is None else kv_len
+    rng = np.random.Generator(np.random.PCG64(seed))
+    nb = -(-N // block)
+    nI = nb - n_text_blocks
+    center_gain = float(np.sqrt(peak / np.sqrt(D)))
+    ck = (rng.standard_normal((B, H, nb, D)) * center_gain).astype(np.float32)
+    cq = np.empty_like(ck)
+    for b in range(B):
+        for h in range(H):
+            perm = np.concatenate([rng.permutation(nI), np.arange(nI, nb)])
+            cq[b, h] = ck[b, h, perm]
+    cq += (rng.standard_normal((B, H, nb, D)) * link_noise).astype(np.float32)
+    out = []
+    for centres in (cq, ck, None):
+        x = rng.standard_normal((B, H, N, D), dtype=np.float32)
+        if centres is not None:
+            x *= np.float32(token_noise)
+            x += np.repeat(centres, block, axis=2)[:, :, :N]
+        bits = f32_to_bf16_bits(x)
+        if kv_len < N:
+            bits[:, :, kv_len:, :] = {"zero": 0, "nan": BF16_NAN, "inf": BF16_INF}[pad_fill]
+        out.append(bits)
+    return tuple(out)
+
+
 # --------------------------------------------------------------------------- masks
 def mask_bernoulli_diag(B, H, nb, p, seed):
     """Each tile kept with probability p; the diagonal forced on."""
@@ -162,6 +197,11 @@ class Workload:
     def qkv(self, pad_fill="zero", gain=1.0):
         return make_qkv(self.B, self.H, self.N, self.D, self.kv_len,
                         seed=self.seed(), gain=gain, pad_fill=pad_fill)
+
+    def qkv_block_structured(self, pad_fill="zero"):
+        """The same shape with a block-structured attention map (what the mask selection is for)."""
+        return make_qkv_block_structured(self.B, self.H, self.N, self.D, self.block, self.kv_len,
+                                         seed=self.seed() + 50, n_text_blocks=self.n_text_blocks, pad_fill=pad_fill)
 
     def mask(self, density):
         """uint8 [B,H,nb,nb] for a nominal density listed in `densities`
