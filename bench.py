@@ -333,7 +333,25 @@ def main():
                                            "achieved": round(gbs, 1), "peak": 8000.0, "unit": "GB/s",
                                            "frac": round(gbs / 8000.0, 4), "algorithmic_bytes": read_bytes,
                                            "achieved_inputs_in_memory_side_cache": round(gbs_c, 1)}}
-        del qk_sets, bq, bk
+        # one layer of a sparse step on the block-structured inputs: selection + attention as two calls
+        # (byte mask in between) and as the one call that writes the kept lists directly
+        tau3 = ra.rapid_mask_level_tau(3)
+        ws1 = torch.empty(ra.rapid_attn_joint_select_workspace_bytes(w.B, w.H, w.N, w.D, w.block), dtype=torch.uint8,
+                          device="cuda")
+        one_seg = [(bq, bk, dv, do)]
+
+        def two_calls():
+            ra.rapid_mask_select(bq, bk, sel_mask, w.block, w.kv_len, text_start, tau3, 0.0, sel_ws)
+            ra.rapid_attn_block_sparse(bq, bk, dv, do, sel_mask, w.block, w.kv_len, 0.0, ws)
+
+        one_call = lambda: ra.rapid_attn_joint_select(one_seg, w.block, kv_len=w.kv_len, text_start=text_start,
+                                                      tau=tau3, workspace=ws1)
+        _, t2 = time_region(two_calls, 100, 10)
+        _, t1 = time_region(one_call, 100, 10)
+        out["mask_select"]["select_and_attend_level_3"] = {
+            "inputs": "block-structured", "kept_fraction": levels[2]["kept_fraction_block_structured_inputs"],
+            "two_calls_ms": round(t2, 5), "one_call_ms": round(t1, 5), "dense_ms": round(ev_mean, 5)}
+        del qk_sets, bq, bk, ws1
 
     # ---- a scripted action trace of one image (counts as in the paper's appendix: 12-16 steps, 4-8 of
     # them reuse the cache, 2-4 run sparse attention) played against the library: the attention side

@@ -96,6 +96,29 @@ RAPID_API int rapid_mask_select_joint(const rapid_attn_segment* segments, int n_
 RAPID_API size_t rapid_mask_select_joint_workspace_bytes(int B, int H, int N, int D, int block);
 
 /*
+ * Selection and attention of one layer in one call (Sec. 3.3 (c): the step's sparse action
+ * drives the attention of every layer): what rapid_mask_select_joint followed by
+ * rapid_attn_joint with that mask computes, but the selection writes the kept key-block
+ * lists straight into the attention's workspace, so no byte mask is written, read back and
+ * compacted in between.
+ *   segments     as rapid_attn_joint (q, k, v, o and all strides are used)
+ *   block, kv_len, kv_lens, text_start, tau   as rapid_mask_select_joint
+ *   scale        of the attention and of the selection scores; <= 0 selects 1/sqrt(D)
+ *   mask_out     device, uint8 [B,H,nb,nb], or NULL: the selected mask, if the caller wants
+ *                to see it (written by the same kernel)
+ *   workspace    at least rapid_attn_joint_select_workspace_bytes(B,H,N,D,block) bytes,
+ *                16-byte aligned; same rules as the workspace of rapid_attn_block_sparse
+ * Errors as rapid_attn_joint and rapid_mask_select_joint.
+ */
+RAPID_API int rapid_attn_joint_select(const rapid_attn_segment* segments, int n_segments,
+                                      int B, int H, int D, int block, int kv_len, const int* kv_lens,
+                                      int text_start, float tau, float scale, unsigned char* mask_out,
+                                      void* workspace, size_t workspace_bytes, void* stream);
+
+/* Workspace bytes of rapid_attn_joint_select; 0 if the shape is invalid or unsupported. */
+RAPID_API size_t rapid_attn_joint_select_workspace_bytes(int B, int H, int N, int D, int block);
+
+/*
  * The library's default tau for a Sparse-Attention action (Sec. 3.3 (c)): action 0
  * (full attention) -> 1.0, actions 1, 2, 3 -> 0.98, 0.95, 0.90 (progressively
  * sparser; values of this library, not of the paper); anything else -> NaN.

@@ -11,6 +11,8 @@ from .binding import (  # noqa: F401
     STATIC_SCRATCH_BYTES,
     rapid_attn_dense,
     rapid_attn_joint,
+    rapid_attn_joint_select,
+    rapid_attn_joint_select_workspace_bytes,
     rapid_attn_joint_workspace_bytes,
     rapid_attn_status_string,
     rapid_attn_version,
@@ -28,7 +30,7 @@ from .binding import (  # noqa: F401
 )
 
 __all__ = [
-    "RapidAttnError", "library", "library_path", "rapid_attn_block_sparse", "rapid_attn_block_sparse_static", "STATIC_SCRATCH_BYTES", "rapid_attn_dense", "rapid_attn_joint", "rapid_attn_joint_workspace_bytes",
+    "RapidAttnError", "library", "library_path", "rapid_attn_block_sparse", "rapid_attn_block_sparse_static", "STATIC_SCRATCH_BYTES", "rapid_attn_dense", "rapid_attn_joint", "rapid_attn_joint_select", "rapid_attn_joint_select_workspace_bytes", "rapid_attn_joint_workspace_bytes",
     "rapid_attn_status_string", "rapid_attn_version", "rapid_attn_workspace_bytes", "rapid_cache_reuse", "rapid_mask_level_tau", "rapid_mask_select", "rapid_mask_select_joint", "rapid_mask_select_joint_workspace_bytes", "rapid_mask_select_workspace_bytes",
     "rapid_cache_store", "rapid_equivalent_steps", "rapid_reward", "STATUS",
 ]

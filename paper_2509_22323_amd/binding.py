@@ -32,7 +32,8 @@ class Segment(ctypes.Structure):
                 ("out_stride_b", ctypes.c_longlong), ("out_stride_h", ctypes.c_longlong),
                 ("out_stride_n", ctypes.c_longlong)]
 MASK_EXPORTS = ("rapid_mask_select", "rapid_mask_select_workspace_bytes", "rapid_mask_select_joint",
-                "rapid_mask_select_joint_workspace_bytes", "rapid_mask_level_tau")
+                "rapid_mask_select_joint_workspace_bytes", "rapid_attn_joint_select",
+                "rapid_attn_joint_select_workspace_bytes", "rapid_mask_level_tau")
 CACHE_EXPORTS = ("rapid_cache_store", "rapid_cache_reuse", "rapid_equivalent_steps", "rapid_reward")
 
 
@@ -92,6 +93,10 @@ def library():
     lib.rapid_mask_select_joint.restype = ci
     lib.rapid_mask_select_joint_workspace_bytes.argtypes = [ci, ci, ci, ci, ci]
     lib.rapid_mask_select_joint_workspace_bytes.restype = sz
+    lib.rapid_attn_joint_select.argtypes = [ctypes.POINTER(Segment), ci, ci, ci, ci, ci, ci, vp, ci, cf, cf, vp, vp, sz, vp]
+    lib.rapid_attn_joint_select.restype = ci
+    lib.rapid_attn_joint_select_workspace_bytes.argtypes = [ci, ci, ci, ci, ci]
+    lib.rapid_attn_joint_select_workspace_bytes.restype = sz
     lib.rapid_mask_level_tau.argtypes = [ci]
     lib.rapid_mask_level_tau.restype = cf
     cd, dp = ctypes.c_double, ctypes.POINTER(ctypes.c_double)
@@ -198,11 +203,8 @@ def rapid_attn_joint_workspace_bytes(B: int, H: int, N: int, D: int, block: int)
     return int(library().rapid_attn_joint_workspace_bytes(B, H, N, D, block))
 
 
-def rapid_attn_joint(segments, mask=None, block=128, kv_len=None, kv_lens=None, scale=0.0, workspace=None):
-    """Joint attention over one or two token segments.  `segments`: sequence of (q, k, v, o),
-    each a CUDA bf16 tensor indexed [B, H, n, D] with a contiguous last dimension and any other
-    strides (a permuted view of a [B, n, H, D] or fused [B, n, 3, H, D] tensor is fine); q, k, v
-    of a segment share their strides.  mask None = dense.  kv_lens: CUDA int32 [B] or None."""
+def _segments(segments):
+    """(descriptor array, B, H, N, D) of a sequence of (q, k, v, o) tensors indexed [B, H, n, D]."""
     import torch
     if len(segments) not in (1, 2):
         raise ValueError("one or two segments")
@@ -227,6 +229,26 @@ def rapid_attn_joint(segments, mask=None, block=128, kv_len=None, kv_lens=None, 
         g.in_stride_b, g.in_stride_h, g.in_stride_n = q.stride(0), q.stride(1), q.stride(2)
         g.out_stride_b, g.out_stride_h, g.out_stride_n = o.stride(0), o.stride(1), o.stride(2)
         N += int(q.shape[2])
+    return descr, B, H, N, D
+
+
+def _kv_lens_ptr(kv_lens, B, device):
+    import torch
+    if kv_lens is None:
+        return None
+    if not (isinstance(kv_lens, torch.Tensor) and kv_lens.is_cuda and kv_lens.dtype == torch.int32
+            and kv_lens.is_contiguous() and kv_lens.numel() == B and kv_lens.device == device):
+        raise TypeError("kv_lens must be a contiguous CUDA int32 tensor [B]")
+    return kv_lens.data_ptr()
+
+
+def rapid_attn_joint(segments, mask=None, block=128, kv_len=None, kv_lens=None, scale=0.0, workspace=None):
+    """Joint attention over one or two token segments.  `segments`: sequence of (q, k, v, o),
+    each a CUDA bf16 tensor indexed [B, H, n, D] with a contiguous last dimension and any other
+    strides (a permuted view of a [B, n, H, D] or fused [B, n, 3, H, D] tensor is fine); q, k, v
+    of a segment share their strides.  mask None = dense.  kv_lens: CUDA int32 [B] or None."""
+    import torch
+    descr, B, H, N, D = _segments(segments)
     q0 = segments[0][0]
     mask_ptr, ws_ptr, ws_bytes = None, None, 0
     if mask is not None:
@@ -240,12 +262,7 @@ def rapid_attn_joint(segments, mask=None, block=128, kv_len=None, kv_lens=None, 
             workspace = torch.empty(max(rapid_attn_joint_workspace_bytes(B, H, N, D, int(block)), 16),
                                     dtype=torch.uint8, device=q0.device)
         mask_ptr, ws_ptr, ws_bytes = mask.data_ptr(), workspace.data_ptr(), workspace.numel() * workspace.element_size()
-    lens_ptr = None
-    if kv_lens is not None:
-        if not (isinstance(kv_lens, torch.Tensor) and kv_lens.is_cuda and kv_lens.dtype == torch.int32
-                and kv_lens.is_contiguous() and kv_lens.numel() == B and kv_lens.device == q0.device):
-            raise TypeError("kv_lens must be a contiguous CUDA int32 tensor [B]")
-        lens_ptr = kv_lens.data_ptr()
+    lens_ptr = _kv_lens_ptr(kv_lens, B, q0.device)
     _check(library().rapid_attn_joint(descr, len(segments), B, H, D, int(block), mask_ptr,
                                       0 if kv_len is None else int(kv_len), lens_ptr, float(scale),
                                       ws_ptr, ws_bytes, _stream(q0)))
@@ -395,3 +412,32 @@ def rapid_mask_select_joint(segments, mask, block, kv_len=None, kv_lens=None, te
         N if text_start is None else int(text_start), float(tau), float(scale), mask.data_ptr(),
         workspace.data_ptr(), workspace.numel() * workspace.element_size(), _stream(q0)))
     return mask
+
+
+def rapid_attn_joint_select_workspace_bytes(B: int, H: int, N: int, D: int, block: int) -> int:
+    return int(library().rapid_attn_joint_select_workspace_bytes(B, H, N, D, block))
+
+
+def rapid_attn_joint_select(segments, block=128, kv_len=None, kv_lens=None, text_start=None, tau=0.95, scale=0.0,
+                            mask_out=None, workspace=None):
+    """Mask selection at `tau` and block-sparse attention under it in one call, on (q, k, v, o)
+    segments as rapid_attn_joint takes them; mask_out: optional CUDA uint8 [B,H,nb,nb] that receives
+    the selected mask.  Returns the o tensors."""
+    import torch
+    descr, B, H, N, D = _segments(segments)
+    q0 = segments[0][0]
+    nb = -(-N // int(block)) if block > 0 else 0
+    mask_ptr = None
+    if mask_out is not None:
+        if not (isinstance(mask_out, torch.Tensor) and mask_out.is_cuda and mask_out.dtype == torch.uint8
+                and mask_out.is_contiguous() and mask_out.device == q0.device and tuple(mask_out.shape) == (B, H, nb, nb)):
+            raise TypeError(f"mask_out must be a contiguous CUDA uint8 tensor {(B, H, nb, nb)}")
+        mask_ptr = mask_out.data_ptr()
+    if workspace is None:
+        workspace = torch.empty(max(rapid_attn_joint_select_workspace_bytes(B, H, N, D, int(block)), 16),
+                                dtype=torch.uint8, device=q0.device)
+    _check(library().rapid_attn_joint_select(
+        descr, len(segments), B, H, D, int(block), 0 if kv_len is None else int(kv_len),
+        _kv_lens_ptr(kv_lens, B, q0.device), N if text_start is None else int(text_start), float(tau), float(scale),
+        mask_ptr, workspace.data_ptr(), workspace.numel() * workspace.element_size(), _stream(q0)))
+    return [seg[3] for seg in segments]

@@ -35,6 +35,8 @@
 #include <initializer_list>
 
 #include "rapid_attn.h"
+#include "rapid_internal.h"
+#include "rapid_mask.h"
 
 // Scratch of the entry point that allocates nothing (see static_scratch below).
 static __device__ __align__(256) unsigned char scratch[RAPID_ATTN_STATIC_SCRATCH_BYTES];
@@ -1766,6 +1768,7 @@ int run_dense(const Problem& pr, void* stream)
 }
 
 // nb = ceil(N / block): the last mask block may be ragged (it then ends at N)
+// `mask` null: counts and lists are already in the workspace (written by the selection kernels)
 int run_sparse(const Problem& pr, int block, const unsigned char* mask, void* workspace, size_t workspace_bytes,
                void* stream, int slots = -1)
 {
@@ -1784,14 +1787,16 @@ int run_sparse(const Problem& pr, int block, const unsigned char* mask, void* wo
     hipStream_t s = (hipStream_t)stream;
 
     const int xcd_items = plan_items(B, H, nb);
-    if (block == 128 && nb <= SMALL_NB && xcd_items <= SMALL_ITEMS && xcd_items * nb <= SMALL_BYTES) {
+    if (mask != nullptr && block == 128 && nb <= SMALL_NB && xcd_items <= SMALL_ITEMS && xcd_items * nb <= SMALL_BYTES) {
         hipLaunchKernelGGL(plan_small_kernel, dim3(XCDS), dim3(1024), 0, s, mask, pr.kv_lens, pr.kv_len, N, block,
                            H, B * H, nb, w.chunk, w.pmax, D, counts, index, (PlanRec*)order,
                            (int32_t*)(ws + w.arrived_off));
     } else {
-        hipLaunchKernelGGL(compact_mask_kernel, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, s,
-                           mask, (int)rows, nb, block, pr.kv_len, pr.kv_lens, H * nb, N, counts, index);
-        if (hipGetLastError() != hipSuccess) return RAPID_ERR_DEVICE;
+        if (mask != nullptr) {
+            hipLaunchKernelGGL(compact_mask_kernel, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, s,
+                               mask, (int)rows, nb, block, pr.kv_len, pr.kv_lens, H * nb, N, counts, index);
+            if (hipGetLastError() != hipSuccess) return RAPID_ERR_DEVICE;
+        }
         if (block == 128)
             hipLaunchKernelGGL(plan_split_kernel, dim3(XCDS), dim3(1024), 0, s, counts, B * H, nb, w.chunk,
                                w.pmax, D, (PlanRec*)order, (int32_t*)(ws + w.arrived_off));
@@ -1831,6 +1836,64 @@ Problem contiguous_problem(const void* q, const void* k, const void* v, void* o,
     pr.kv_len = kv_len; pr.kv_lens = nullptr;
     pr.scale = scale > 0.f ? scale : 1.0f / sqrtf((float)D);
     return pr;
+}
+
+// The segments of rapid_attn_joint as a validated Problem.
+int joint_problem(const rapid_attn_segment* segments, int n_segments, int B, int H, int D, int block, bool sparse,
+                  int kv_len, const int* kv_lens, float scale, Problem& pr)
+{
+    if (!segments) return RAPID_ERR_NULL;
+    if (n_segments != 1 && n_segments != 2) return RAPID_ERR_SHAPE;
+    if (B <= 0 || H <= 0) return RAPID_ERR_SHAPE;
+    if (D != 64 && D != 128) return RAPID_ERR_UNSUPPORTED;
+    if (sparse && block != 64 && block != 128) return RAPID_ERR_UNSUPPORTED;
+    long long N = 0;
+    for (int i = 0; i < n_segments; ++i) {
+        const rapid_attn_segment& g = segments[i];
+        if (!g.q || !g.k || !g.v || !g.o) return RAPID_ERR_NULL;
+        if (g.n <= 0) return RAPID_ERR_SHAPE;
+        if (!aligned16(g.q) || !aligned16(g.k) || !aligned16(g.v) || !aligned16(g.o)) return RAPID_ERR_ALIGN;
+        const long long st[6] = {g.in_stride_b, g.in_stride_h, g.in_stride_n, g.out_stride_b, g.out_stride_h, g.out_stride_n};
+        for (int j = 0; j < 6; ++j) {
+            if (st[j] < 0 || st[j] > (1LL << 40)) return RAPID_ERR_SHAPE;
+            if (st[j] % 8 != 0) return RAPID_ERR_ALIGN;            // every row starts on 16 bytes
+        }
+        // rows are D contiguous elements; byte offsets inside a 64-row tile stay below 2^31
+        if (g.in_stride_n < D || g.out_stride_n < D || g.in_stride_n > (1LL << 23) || g.out_stride_n > (1LL << 23)) return RAPID_ERR_SHAPE;
+        N += g.n;
+    }
+    if (N > (1 << 22)) return RAPID_ERR_SHAPE;
+    if ((long long)B * H > 0x7fffffffLL / 4096) return RAPID_ERR_SHAPE;
+    if (n_segments == 2) {
+        // tiles of 64 keys and mask blocks of 128 queries must not straddle the two tensors
+        if (segments[0].n % 128 != 0) return RAPID_ERR_SHAPE;
+        if (segments[0].in_stride_h != segments[1].in_stride_h || segments[0].in_stride_n != segments[1].in_stride_n ||
+            segments[0].out_stride_h != segments[1].out_stride_h || segments[0].out_stride_n != segments[1].out_stride_n)
+            return RAPID_ERR_SHAPE;
+    }
+    if (kv_len == 0) kv_len = (int)N;
+    if (kv_len < 1 || kv_len > N) return RAPID_ERR_SHAPE;
+
+    auto view = [&](int which) {
+        SegTensor t;
+        const rapid_attn_segment& a = segments[0];
+        const rapid_attn_segment* b2 = n_segments == 2 ? &segments[1] : nullptr;
+        const void* p0 = which == 0 ? a.q : which == 1 ? a.k : which == 2 ? a.v : (const void*)a.o;
+        const void* p1 = !b2 ? nullptr : which == 0 ? b2->q : which == 1 ? b2->k : which == 2 ? b2->v : (const void*)b2->o;
+        t.seg0 = (const __bf16*)p0; t.seg1 = (const __bf16*)p1;
+        const bool out = which == 3;
+        t.sb0 = out ? a.out_stride_b : a.in_stride_b;
+        t.sb1 = !b2 ? 0 : (out ? b2->out_stride_b : b2->in_stride_b);
+        t.sh = out ? a.out_stride_h : a.in_stride_h;
+        t.sn = out ? a.out_stride_n : a.in_stride_n;
+        return t;
+    };
+    pr.q = view(0); pr.k = view(1); pr.v = view(2); pr.o = view(3);
+    pr.n0 = n_segments == 2 ? segments[0].n : (int)N;
+    pr.B = B; pr.H = H; pr.N = (int)N; pr.D = D;
+    pr.kv_len = kv_len; pr.kv_lens = kv_lens;
+    pr.scale = scale > 0.f ? scale : 1.0f / sqrtf((float)D);
+    return RAPID_OK;
 }
 
 // The scratch of rapid_attn_block_sparse_static: one array per GPU, part of the loaded code
@@ -1885,60 +1948,41 @@ int rapid_attn_joint(const rapid_attn_segment* segments, int n_segments, int B, 
                      int block, const unsigned char* mask, int kv_len, const int* kv_lens, float scale,
                      void* workspace, size_t workspace_bytes, void* stream)
 {
-    if (!segments) return RAPID_ERR_NULL;
-    if (n_segments != 1 && n_segments != 2) return RAPID_ERR_SHAPE;
-    if (B <= 0 || H <= 0) return RAPID_ERR_SHAPE;
-    if (D != 64 && D != 128) return RAPID_ERR_UNSUPPORTED;
-    if (mask && block != 64 && block != 128) return RAPID_ERR_UNSUPPORTED;
-    long long N = 0;
-    for (int i = 0; i < n_segments; ++i) {
-        const rapid_attn_segment& g = segments[i];
-        if (!g.q || !g.k || !g.v || !g.o) return RAPID_ERR_NULL;
-        if (g.n <= 0) return RAPID_ERR_SHAPE;
-        if (!aligned16(g.q) || !aligned16(g.k) || !aligned16(g.v) || !aligned16(g.o)) return RAPID_ERR_ALIGN;
-        const long long st[6] = {g.in_stride_b, g.in_stride_h, g.in_stride_n, g.out_stride_b, g.out_stride_h, g.out_stride_n};
-        for (int j = 0; j < 6; ++j) {
-            if (st[j] < 0 || st[j] > (1LL << 40)) return RAPID_ERR_SHAPE;
-            if (st[j] % 8 != 0) return RAPID_ERR_ALIGN;            // every row starts on 16 bytes
-        }
-        // rows are D contiguous elements; byte offsets inside a 64-row tile stay below 2^31
-        if (g.in_stride_n < D || g.out_stride_n < D || g.in_stride_n > (1LL << 23) || g.out_stride_n > (1LL << 23)) return RAPID_ERR_SHAPE;
-        N += g.n;
-    }
-    if (N > (1 << 22)) return RAPID_ERR_SHAPE;
-    if ((long long)B * H > 0x7fffffffLL / 4096) return RAPID_ERR_SHAPE;
-    if (n_segments == 2) {
-        // tiles of 64 keys and mask blocks of 128 queries must not straddle the two tensors
-        if (segments[0].n % 128 != 0) return RAPID_ERR_SHAPE;
-        if (segments[0].in_stride_h != segments[1].in_stride_h || segments[0].in_stride_n != segments[1].in_stride_n ||
-            segments[0].out_stride_h != segments[1].out_stride_h || segments[0].out_stride_n != segments[1].out_stride_n)
-            return RAPID_ERR_SHAPE;
-    }
-    if (kv_len == 0) kv_len = (int)N;
-    if (kv_len < 1 || kv_len > N) return RAPID_ERR_SHAPE;
-
     Problem pr;
-    auto view = [&](int which) {
-        SegTensor t;
-        const rapid_attn_segment& a = segments[0];
-        const rapid_attn_segment* b2 = n_segments == 2 ? &segments[1] : nullptr;
-        const void* p0 = which == 0 ? a.q : which == 1 ? a.k : which == 2 ? a.v : (const void*)a.o;
-        const void* p1 = !b2 ? nullptr : which == 0 ? b2->q : which == 1 ? b2->k : which == 2 ? b2->v : (const void*)b2->o;
-        t.seg0 = (const __bf16*)p0; t.seg1 = (const __bf16*)p1;
-        const bool out = which == 3;
-        t.sb0 = out ? a.out_stride_b : a.in_stride_b;
-        t.sb1 = !b2 ? 0 : (out ? b2->out_stride_b : b2->in_stride_b);
-        t.sh = out ? a.out_stride_h : a.in_stride_h;
-        t.sn = out ? a.out_stride_n : a.in_stride_n;
-        return t;
-    };
-    pr.q = view(0); pr.k = view(1); pr.v = view(2); pr.o = view(3);
-    pr.n0 = n_segments == 2 ? segments[0].n : (int)N;
-    pr.B = B; pr.H = H; pr.N = (int)N; pr.D = D;
-    pr.kv_len = kv_len; pr.kv_lens = kv_lens;
-    pr.scale = scale > 0.f ? scale : 1.0f / sqrtf((float)D);
+    const int rc = joint_problem(segments, n_segments, B, H, D, block, mask != nullptr, kv_len, kv_lens, scale, pr);
+    if (rc != RAPID_OK) return rc;
     if (!mask) return run_dense(pr, stream);
     return run_sparse(pr, block, mask, workspace, workspace_bytes, stream);
+}
+
+// Selection and attention in one call: the selection kernels write counts and kept lists where the
+// attention's own compaction would have put them; the block means go behind the attention workspace.
+int rapid_attn_joint_select(const rapid_attn_segment* segments, int n_segments, int B, int H, int D, int block,
+                            int kv_len, const int* kv_lens, int text_start, float tau, float scale,
+                            unsigned char* mask_out, void* workspace, size_t workspace_bytes, void* stream)
+{
+    Problem pr;
+    const int rc = joint_problem(segments, n_segments, B, H, D, block, true, kv_len, kv_lens, scale, pr);
+    if (rc != RAPID_OK) return rc;
+    const int nb = (pr.N + block - 1) / block;
+    if ((long long)B * H * nb > 0x7fffffffLL / 16) return RAPID_ERR_SHAPE;
+    const WorkspaceLayout w = workspace_layout(B, H, nb, D, block);
+    const size_t means = rapid_internal::select_scratch_bytes(B, H, nb, D);
+    if (!workspace || workspace_bytes < w.total + means) return RAPID_ERR_WORKSPACE;
+    if (!aligned16(workspace)) return RAPID_ERR_ALIGN;
+    char* ws = (char*)workspace;
+    const int rs = rapid_internal::select_to_lists(segments, n_segments, B, H, D, block, kv_len, kv_lens, text_start, tau,
+                                                   scale, mask_out, (int32_t*)(ws + w.counts_off),
+                                                   (int32_t*)(ws + w.index_off), ws + w.total, means, stream);
+    if (rs != RAPID_OK) return rs;
+    return run_sparse(pr, block, nullptr, workspace, w.total, stream);
+}
+
+size_t rapid_attn_joint_select_workspace_bytes(int B, int H, int N, int D, int block)
+{
+    const size_t attn = rapid_attn_joint_workspace_bytes(B, H, N, D, block);
+    if (attn == 0 || (N + block - 1) / block > 2048) return 0;
+    return attn + rapid_internal::select_scratch_bytes(B, H, (N + block - 1) / block, D);
 }
 
 int rapid_attn_block_sparse_static(const void* q, const void* k, const void* v, void* o,

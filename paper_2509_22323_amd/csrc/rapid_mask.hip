@@ -11,6 +11,7 @@
 #include <math.h>
 #include <stdint.h>
 
+#include "rapid_internal.h"
 #include "rapid_mask.h"
 
 namespace {
@@ -101,10 +102,38 @@ __device__ __forceinline__ float wave_sum(float v)
 }
 
 // One wavefront per mask row (b, h, i); four rows per workgroup.
+// What a row's result is written as: a byte per key-block into `mask` (when given), and/or the
+// ascending list of kept key-blocks with its length (the form the attention kernels walk: the
+// arrays `counts` and `index` of the attention workspace), so that selection can feed the
+// attention without a byte mask in between.
+struct RowSink {
+    unsigned char* mask;     // [rows, nb] or null
+    int32_t* counts;         // [rows] or null
+    int32_t* index;          // [rows, nb], with counts
+};
+
+// One wavefront writes row `row`: keep(j) for j = lane, lane + 64, ...; every lane takes part.
+template <class Keep>
+__device__ __forceinline__ void write_row(const RowSink& sink, size_t row, int nb, int lane, Keep keep)
+{
+    int base = 0;
+    for (int j0 = 0; j0 < nb; j0 += 64) {
+        const int j = j0 + lane;
+        const bool kp = j < nb && keep(j);
+        if (sink.mask != nullptr && j < nb) sink.mask[row * nb + j] = kp ? 1 : 0;
+        if (sink.counts != nullptr) {
+            const unsigned long long bal = __ballot(kp);
+            if (kp) sink.index[row * nb + base + __popcll(bal & ((1ull << lane) - 1ull))] = j;
+            base += __popcll(bal);
+        }
+    }
+    if (sink.counts != nullptr && lane == 0) sink.counts[row] = base;
+}
+
 template <int D>
 __global__ __launch_bounds__(256) void select_blocks_kernel(const float* __restrict__ qmean, const float* __restrict__ kmean,
                                                             const QKView v, int block, int rows, int nb, float tau,
-                                                            float scale, unsigned char* __restrict__ mask)
+                                                            float scale, const RowSink sink)
 {
     __shared__ float qrow[4][D];
     __shared__ float prob[4][MAX_NB];
@@ -115,9 +144,8 @@ __global__ __launch_bounds__(256) void select_blocks_kernel(const float* __restr
     const size_t bh = row / nb;
     int live, first_text;
     sample_blocks(v, (int)(bh / v.H), block, nb, live, first_text);
-    unsigned char* out = mask + (size_t)row * nb;
     if (i >= live) {
-        for (int j = lane; j < nb; j += 64) out[j] = 0;
+        write_row(sink, (size_t)row, nb, lane, [](int) { return false; });
         return;
     }
     for (int d = lane; d < D; d += 64) qrow[wv][d] = qmean[(size_t)row * D + d];
@@ -171,11 +199,9 @@ __global__ __launch_bounds__(256) void select_blocks_kernel(const float* __restr
         cut = lo;
     }
     const bool text_row = i >= first_text;
-    for (int j = lane; j < nb; j += 64) {
-        bool keep = false;
-        if (j < live) keep = text_row || j >= first_text || j == i || __float_as_uint(prob[wv][j]) >= cut;
-        out[j] = keep ? 1 : 0;
-    }
+    write_row(sink, (size_t)row, nb, lane, [&](int j) {
+        return j < live && (text_row || j >= first_text || j == i || __float_as_uint(prob[wv][j]) >= cut);
+    });
 }
 
 // The same for up to SMALL_NB mask blocks per side (every shape of the paper's models): one
@@ -193,7 +219,7 @@ template <int D>
 __global__ __launch_bounds__(256) void select_blocks_small_kernel(const float* __restrict__ qmean,
                                                                   const float* __restrict__ kmean, const QKView v,
                                                                   int block, int nb, float tau, float scale,
-                                                                  unsigned char* __restrict__ mask)
+                                                                  const RowSink sink)
 {
     constexpr int KROW = D + 4;
     __shared__ __attribute__((aligned(16))) float kch[64 * KROW];
@@ -257,9 +283,9 @@ __global__ __launch_bounds__(256) void select_blocks_small_kernel(const float* _
     for (int r = 0; r < SMALL_RPW; ++r) {
         const int row = wv * SMALL_RPW + r, i = i0 + row;
         if (i >= nb) break;
-        unsigned char* out = mask + (bh * nb + i) * (size_t)nb;
+        const size_t mrow = bh * nb + i;
         if (i >= live) {
-            for (int j = lane; j < nb; j += 64) out[j] = 0;
+            write_row(sink, mrow, nb, lane, [](int) { return false; });
             continue;
         }
         float mx = -INFINITY;
@@ -273,22 +299,17 @@ __global__ __launch_bounds__(256) void select_blocks_small_kernel(const float* _
         }
         const float target = tau * wave_sum(part);
         const bool text_row = i >= first_text;
-        for (int j = lane; j < nb; j += 64) {
-            bool keep = false;
-            if (j < live) {
-                keep = text_row || j >= first_text || j == i || tau >= 1.0f;
-                if (!keep) {
-                    const float mine = ps[row][j];
-                    float above = 0.f;                         // mass of the blocks that come before j
-                    for (int k2 = 0; k2 < live; ++k2) {
-                        const float e = ps[row][k2];
-                        above += (e > mine) ? e : 0.f;
-                    }
-                    keep = above < target;
-                }
+        write_row(sink, mrow, nb, lane, [&](int j) {
+            if (j >= live) return false;
+            if (text_row || j >= first_text || j == i || tau >= 1.0f) return true;
+            const float mine = ps[row][j];
+            float above = 0.f;                             // mass of the blocks that come before j
+            for (int k2 = 0; k2 < live; ++k2) {
+                const float e = ps[row][k2];
+                above += (e > mine) ? e : 0.f;
             }
-            out[j] = keep ? 1 : 0;
-        }
+            return above < target;
+        });
     }
 }
 
@@ -308,7 +329,7 @@ bool shape_ok(int B, int H, int N, int D, int block, bool ragged)
 }
 
 // One validated call: means, then the selection kernel that fits the size.
-int run_select(const QKView& v, int B, int D, int block, float tau, float scale, unsigned char* mask, void* workspace,
+int run_select(const QKView& v, int B, int D, int block, float tau, float scale, const RowSink& sink, void* workspace,
                size_t workspace_bytes, void* stream)
 {
     const int H = v.H, nb = (v.N + block - 1) / block;
@@ -332,23 +353,85 @@ int run_select(const QKView& v, int B, int D, int block, float tau, float scale,
         const dim3 gs((unsigned)(B * H * ((nb + SMALL_ROWS - 1) / SMALL_ROWS)));
         if (D == 64)
             hipLaunchKernelGGL((select_blocks_small_kernel<64>), gs, dim3(256), 0, s, means, means + which_stride, v, block,
-                               nb, tau, scale, mask);
+                               nb, tau, scale, sink);
         else
             hipLaunchKernelGGL((select_blocks_small_kernel<128>), gs, dim3(256), 0, s, means, means + which_stride, v, block,
-                               nb, tau, scale, mask);
+                               nb, tau, scale, sink);
         return hipGetLastError() == hipSuccess ? RAPID_OK : RAPID_ERR_DEVICE;
     }
     const dim3 g2((unsigned)((rows + 3) / 4));
     if (D == 64)
         hipLaunchKernelGGL((select_blocks_kernel<64>), g2, dim3(256), 0, s, means, means + which_stride, v, block, rows, nb,
-                           tau, scale, mask);
+                           tau, scale, sink);
     else
         hipLaunchKernelGGL((select_blocks_kernel<128>), g2, dim3(256), 0, s, means, means + which_stride, v, block, rows, nb,
-                           tau, scale, mask);
+                           tau, scale, sink);
     return hipGetLastError() == hipSuccess ? RAPID_OK : RAPID_ERR_DEVICE;
 }
 
+// Q and K of the joint sequence from segment descriptors, validated (v and o are not looked at).
+int joint_view(const rapid_attn_segment* segments, int n_segments, int B, int H, int D, int block, int kv_len,
+               const int* kv_lens, int text_start, float tau, QKView& v)
+{
+    if (!segments) return RAPID_ERR_NULL;
+    if (n_segments != 1 && n_segments != 2) return RAPID_ERR_SHAPE;
+    if (B <= 0 || H <= 0) return RAPID_ERR_SHAPE;
+    if ((long long)B * H > 0x7fffffffLL / 4096) return RAPID_ERR_SHAPE;
+    if (D != 64 && D != 128) return RAPID_ERR_UNSUPPORTED;
+    if (block != 64 && block != 128) return RAPID_ERR_UNSUPPORTED;
+    if (text_start < 0 || !(tau > 0.f)) return RAPID_ERR_SHAPE;
+    long long N = 0;
+    for (int i = 0; i < n_segments; ++i) {
+        const rapid_attn_segment& g = segments[i];
+        if (!g.q || !g.k) return RAPID_ERR_NULL;
+        if (g.n <= 0) return RAPID_ERR_SHAPE;
+        if (!aligned16(g.q) || !aligned16(g.k)) return RAPID_ERR_ALIGN;
+        const long long st[3] = {g.in_stride_b, g.in_stride_h, g.in_stride_n};
+        for (int j = 0; j < 3; ++j) {
+            if (st[j] < 0 || st[j] > (1LL << 40)) return RAPID_ERR_SHAPE;
+            if (st[j] % 8 != 0) return RAPID_ERR_ALIGN;        // every row starts on 16 bytes
+        }
+        if (g.in_stride_n < D || g.in_stride_n > (1LL << 23)) return RAPID_ERR_SHAPE;
+        N += g.n;
+    }
+    if (N > (1 << 22)) return RAPID_ERR_SHAPE;
+    if (n_segments == 2) {
+        // as rapid_attn_joint: the masks made here are for that call
+        if (segments[0].n % 128 != 0) return RAPID_ERR_SHAPE;
+        if (segments[0].in_stride_h != segments[1].in_stride_h || segments[0].in_stride_n != segments[1].in_stride_n)
+            return RAPID_ERR_SHAPE;
+    }
+    if (kv_len == 0) kv_len = (int)N;
+    if (kv_len < 1 || kv_len > N) return RAPID_ERR_SHAPE;
+    v.q0 = (const uint16_t*)segments[0].q; v.k0 = (const uint16_t*)segments[0].k;
+    v.q1 = n_segments == 2 ? (const uint16_t*)segments[1].q : nullptr;
+    v.k1 = n_segments == 2 ? (const uint16_t*)segments[1].k : nullptr;
+    v.sb0 = segments[0].in_stride_b; v.sb1 = n_segments == 2 ? segments[1].in_stride_b : 0;
+    v.sh = segments[0].in_stride_h; v.sn = segments[0].in_stride_n;
+    v.n0 = n_segments == 2 ? segments[0].n : (int)N; v.N = (int)N; v.H = H;
+    v.kv_len = kv_len; v.kv_lens = kv_lens; v.text_start = text_start;
+    return RAPID_OK;
+}
+
 }  // namespace
+
+namespace rapid_internal {
+
+size_t select_scratch_bytes(int B, int H, int nb, int D) { return means_bytes(B, H, nb, D); }
+
+int select_to_lists(const rapid_attn_segment* segments, int n_segments, int B, int H, int D, int block,
+                    int kv_len, const int* kv_lens, int text_start, float tau, float scale,
+                    unsigned char* mask, int32_t* counts, int32_t* index, void* scratch, size_t scratch_bytes,
+                    void* stream)
+{
+    if (!counts || !index) return RAPID_ERR_NULL;
+    QKView v{};
+    const int rc = joint_view(segments, n_segments, B, H, D, block, kv_len, kv_lens, text_start, tau, v);
+    if (rc != RAPID_OK) return rc;
+    return run_select(v, B, D, block, tau, scale, RowSink{mask, counts, index}, scratch, scratch_bytes, stream);
+}
+
+}  // namespace rapid_internal
 
 extern "C" {
 
@@ -370,52 +453,18 @@ int rapid_mask_select(const void* q, const void* k, int B, int H, int N, int D, 
     v.sb0 = (long long)H * N * D; v.sb1 = 0; v.sh = (long long)N * D; v.sn = D;
     v.n0 = N; v.N = N; v.H = H;
     v.kv_len = kv_len; v.kv_lens = nullptr; v.text_start = text_start;
-    return run_select(v, B, D, block, tau, scale, mask, workspace, workspace_bytes, stream);
+    return run_select(v, B, D, block, tau, scale, RowSink{mask, nullptr, nullptr}, workspace, workspace_bytes, stream);
 }
 
 int rapid_mask_select_joint(const rapid_attn_segment* segments, int n_segments, int B, int H, int D, int block,
                             int kv_len, const int* kv_lens, int text_start, float tau, float scale,
                             unsigned char* mask, void* workspace, size_t workspace_bytes, void* stream)
 {
-    if (!segments || !mask) return RAPID_ERR_NULL;
-    if (n_segments != 1 && n_segments != 2) return RAPID_ERR_SHAPE;
-    if (B <= 0 || H <= 0) return RAPID_ERR_SHAPE;
-    if ((long long)B * H > 0x7fffffffLL / 4096) return RAPID_ERR_SHAPE;
-    if (D != 64 && D != 128) return RAPID_ERR_UNSUPPORTED;
-    if (block != 64 && block != 128) return RAPID_ERR_UNSUPPORTED;
-    if (text_start < 0 || !(tau > 0.f)) return RAPID_ERR_SHAPE;
-    long long N = 0;
-    for (int i = 0; i < n_segments; ++i) {
-        const rapid_attn_segment& g = segments[i];
-        if (!g.q || !g.k) return RAPID_ERR_NULL;               // v and o are not read
-        if (g.n <= 0) return RAPID_ERR_SHAPE;
-        if (!aligned16(g.q) || !aligned16(g.k)) return RAPID_ERR_ALIGN;
-        const long long st[3] = {g.in_stride_b, g.in_stride_h, g.in_stride_n};
-        for (int j = 0; j < 3; ++j) {
-            if (st[j] < 0 || st[j] > (1LL << 40)) return RAPID_ERR_SHAPE;
-            if (st[j] % 8 != 0) return RAPID_ERR_ALIGN;        // every row starts on 16 bytes
-        }
-        if (g.in_stride_n < D || g.in_stride_n > (1LL << 23)) return RAPID_ERR_SHAPE;
-        N += g.n;
-    }
-    if (N > (1 << 22)) return RAPID_ERR_SHAPE;
-    if (n_segments == 2) {
-        // as rapid_attn_joint: the masks made here are for that call
-        if (segments[0].n % 128 != 0) return RAPID_ERR_SHAPE;
-        if (segments[0].in_stride_h != segments[1].in_stride_h || segments[0].in_stride_n != segments[1].in_stride_n)
-            return RAPID_ERR_SHAPE;
-    }
-    if (kv_len == 0) kv_len = (int)N;
-    if (kv_len < 1 || kv_len > N) return RAPID_ERR_SHAPE;
+    if (!mask) return RAPID_ERR_NULL;
     QKView v{};
-    v.q0 = (const uint16_t*)segments[0].q; v.k0 = (const uint16_t*)segments[0].k;
-    v.q1 = n_segments == 2 ? (const uint16_t*)segments[1].q : nullptr;
-    v.k1 = n_segments == 2 ? (const uint16_t*)segments[1].k : nullptr;
-    v.sb0 = segments[0].in_stride_b; v.sb1 = n_segments == 2 ? segments[1].in_stride_b : 0;
-    v.sh = segments[0].in_stride_h; v.sn = segments[0].in_stride_n;
-    v.n0 = n_segments == 2 ? segments[0].n : (int)N; v.N = (int)N; v.H = H;
-    v.kv_len = kv_len; v.kv_lens = kv_lens; v.text_start = text_start;
-    return run_select(v, B, D, block, tau, scale, mask, workspace, workspace_bytes, stream);
+    const int rc = joint_view(segments, n_segments, B, H, D, block, kv_len, kv_lens, text_start, tau, v);
+    if (rc != RAPID_OK) return rc;
+    return run_select(v, B, D, block, tau, scale, RowSink{mask, nullptr, nullptr}, workspace, workspace_bytes, stream);
 }
 
 size_t rapid_mask_select_workspace_bytes(int B, int H, int N, int D, int block)

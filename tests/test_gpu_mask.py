@@ -177,3 +177,73 @@ def test_joint_select_then_joint_attend_on_the_same_tensors():
     for b in range(B):
         ref = oracle_joint(q[b:b + 1], k[b:b + 1], v[b:b + 1], int(lens[b]), mask[b:b + 1], block)
         assert_close(got[b:b + 1], ref, f"sample {b}")
+
+
+SELECT_ATTEND = [
+    # B, H, n_img, n_txt, D, block, lens, fused
+    (2, 3, 1024, 154, 128, 128, (1178, 1118), True),      # ragged last block, per-sample lengths
+    (1, 24, 4096, 512, 128, 128, None, True),             # the FLUX-like 1024^2 joint shape: one-launch planner size
+    (2, 2, 512, 64, 64, 64, (576, 0), False),             # 64-token tiles, an empty sample
+    (1, 3, 8192, 256, 64, 128, None, False),              # 66 blocks per side: the general planner either way
+]
+
+
+@pytest.mark.parametrize("B,H,n_img,n_txt,D,block,lens,fused", SELECT_ATTEND)
+def test_select_and_attend_in_one_call(B, H, n_img, n_txt, D, block, lens, fused):
+    """rapid_attn_joint_select against its two-call form: the mask it reports equals the one
+    rapid_mask_select_joint writes (same kernel, same arithmetic: bit for bit), the kept lists it
+    left in the workspace are that mask compacted (the oracle's kept_tiles of it), and the output
+    matches the oracle's attention under that mask."""
+    import oracle
+    from gpu_common import assert_close
+    from test_gpu_joint import as_model_tensors, gather, oracle_joint
+    from test_gpu_parity import read_plan, check_plan
+    tau = 0.9
+    N = n_img + n_txt
+    nb = -(-N // block)
+    lens_h = np.array([N] * B if lens is None else lens, np.int32)
+    dl = torch.from_numpy(lens_h).cuda()
+    q, k, v = wl.make_qkv_block_structured(B, H, N, D, block, seed=N + 3 * D, n_text_blocks=-(-n_txt // block))
+    segs, guards = as_model_tensors(q, k, v, n_img, fused)
+    m_two = torch.full((B, H, nb, nb), 9, dtype=torch.uint8, device="cuda")
+    ra.rapid_mask_select_joint(segs, m_two, block, kv_lens=dl, text_start=n_img, tau=tau)
+    ra.rapid_attn_joint(segs, m_two, block, kv_lens=dl)
+    torch.cuda.synchronize()
+    want = gather(segs)
+
+    segs1, guards1 = as_model_tensors(q, k, v, n_img, fused)
+    m_one = torch.full((B, H, nb, nb), 9, dtype=torch.uint8, device="cuda")
+    ws = torch.full((ra.rapid_attn_joint_select_workspace_bytes(B, H, N, D, block),), 0xAB, dtype=torch.uint8, device="cuda")
+    ra.rapid_attn_joint_select(segs1, block, kv_lens=dl, text_start=n_img, tau=tau, mask_out=m_one, workspace=ws)
+    torch.cuda.synchronize()
+    mask = m_one.cpu().numpy()
+    np.testing.assert_array_equal(mask, m_two.cpu().numpy())
+    assert 0.15 < mask[lens_h.argmax()].mean() < 0.9
+    got = gather(segs1)
+    # lists and plan left in the workspace: the mask compacted, a valid plan
+    counts, order, index, g = read_plan(ws.cpu().numpy(), B, H, nb, D, block)
+    for b in range(B):
+        wc, wi = oracle.kept_tiles(mask[b:b + 1], block, max(int(lens_h[b]), 1))
+        rows = slice(b * H * nb, (b + 1) * H * nb)
+        np.testing.assert_array_equal(counts[rows], wc.reshape(-1) if lens_h[b] > 0 else 0)
+        if lens_h[b] > 0:
+            wi = wi.reshape(-1, nb)
+            for r in range(H * nb):
+                np.testing.assert_array_equal(index[rows][r, :wc.reshape(-1)[r]], wi[r, :wc.reshape(-1)[r]])
+    check_plan(counts, order, g, B, H, nb, block, D)
+    # output: the oracle under the selected mask; and the two-call form to rounding (its planner may
+    # cut rows differently, so not bit for bit)
+    for b in range(B):
+        if lens_h[b] == 0:
+            assert (got[b] == 0).all()
+            continue
+        ref = oracle_joint(q[b:b + 1], k[b:b + 1], v[b:b + 1], int(lens_h[b]), mask[b:b + 1], block)
+        assert_close(got[b:b + 1], ref, f"one call, sample {b}")
+        assert_close(want[b:b + 1], ref, f"two calls, sample {b}")
+    for gbuf in guards1:
+        assert (gbuf[:, :, 0] == 7.0).all() and (gbuf[:, :, -1] == 7.0).all()
+    # without mask_out the same output
+    segs2, _ = as_model_tensors(q, k, v, n_img, fused)
+    ra.rapid_attn_joint_select(segs2, block, kv_lens=dl, text_start=n_img, tau=tau, workspace=ws)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(gather(segs2), got)

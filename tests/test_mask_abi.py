@@ -81,3 +81,30 @@ def test_joint_selection_argument_errors_come_before_any_launch():
     assert joint([seg(n=256), seg(n=77)], ws=None) == S["RAPID_ERR_WORKSPACE"]
     assert joint([seg(n=256), seg(n=77)], ws_bytes=need - 1) == S["RAPID_ERR_WORKSPACE"]
     assert ra.rapid_mask_select_joint_workspace_bytes(1, 2, 0, 64, 128) == 0
+
+
+def test_select_and_attend_argument_errors_come_before_any_launch():
+    S = ra.STATUS
+
+    def full(n=256, **over):
+        g = seg(n=n, **over)
+        g.v, g.o = g.v or A + 0x200000, g.o or A + 0x300000
+        g.out_stride_b, g.out_stride_h, g.out_stride_n = n * 2 * 64, 64, 2 * 64
+        return g
+
+    def one(segs, B=1, H=2, D=64, block=128, kv_len=0, text_start=256, tau=0.9, ws=WS, ws_bytes=1 << 30):
+        arr = (binding.Segment * max(len(segs), 1))(*segs)
+        return ra.library().rapid_attn_joint_select(arr if segs else None, len(segs), B, H, D, block, kv_len, None,
+                                                    text_start, tau, 0.0, None, ws, ws_bytes, None)
+
+    assert one([]) == S["RAPID_ERR_NULL"]
+    g = full(); g.v = None
+    assert one([g]) == S["RAPID_ERR_NULL"]                                   # v is needed here
+    assert one([full()], tau=0.0) == S["RAPID_ERR_SHAPE"] and one([full()], kv_len=300) == S["RAPID_ERR_SHAPE"]
+    assert one([full()], block=32) == S["RAPID_ERR_UNSUPPORTED"] and one([full()], D=96) == S["RAPID_ERR_UNSUPPORTED"]
+    assert one([full(n=200), full(n=77)]) == S["RAPID_ERR_SHAPE"]
+    need = ra.rapid_attn_joint_select_workspace_bytes(1, 2, 256, 64, 128)
+    assert need == ra.rapid_attn_joint_workspace_bytes(1, 2, 256, 64, 128) + ra.rapid_mask_select_joint_workspace_bytes(1, 2, 256, 64, 128)
+    assert one([full()], ws=None) == S["RAPID_ERR_WORKSPACE"] and one([full()], ws_bytes=need - 1) == S["RAPID_ERR_WORKSPACE"]
+    assert one([full()], ws=WS + 4) == S["RAPID_ERR_ALIGN"]
+    assert ra.rapid_attn_joint_select_workspace_bytes(1, 2, 0, 64, 128) == 0
