@@ -85,6 +85,11 @@ def parse():
     ap.add_argument("--only-attention", action="store_true",
                     help="time the dense call and the sparse densities of --workload and nothing else "
                          "(what the per-kernel profiles under profiles/ are taken from)")
+    ap.add_argument("--only-cache-case", type=int, default=None,
+                    help="time only the Cache-Reuse kernels on tensor case 0, 1 or 2 (latent / one layer / 8 layers) "
+                         "and nothing else besides the headline leg (for per-size profiles)")
+    ap.add_argument("--only-mask-select", action="store_true",
+                    help="time only the mask selection besides the headline leg (for its profile)")
     ap.add_argument("--density", default=None,
                     help="with --only-attention: time only this nominal density of the sparse entry point")
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
@@ -99,6 +104,11 @@ def main():
     if args.only_attention:
         args.no_cpu_baseline = args.no_mfma_probe = args.no_cache_ops = args.no_joint = True
         args.no_mask_select = args.no_trace = args.no_configs = True
+    if args.only_cache_case is not None or args.only_mask_select:
+        args.no_cpu_baseline = args.no_mfma_probe = args.no_joint = args.no_sparse = True
+        args.no_trace = args.no_configs = True
+        args.no_cache_ops = args.only_cache_case is None
+        args.no_mask_select = not args.only_mask_select
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus above 1 is not supported "
               "(no collectives or sharding are part of it).", file=sys.stderr)
@@ -333,25 +343,27 @@ def main():
                                            "achieved": round(gbs, 1), "peak": 8000.0, "unit": "GB/s",
                                            "frac": round(gbs / 8000.0, 4), "algorithmic_bytes": read_bytes,
                                            "achieved_inputs_in_memory_side_cache": round(gbs_c, 1)}}
-        # one layer of a sparse step on the block-structured inputs: selection + attention as two calls
-        # (byte mask in between) and as the one call that writes the kept lists directly
-        tau3 = ra.rapid_mask_level_tau(3)
-        ws1 = torch.empty(ra.rapid_attn_joint_select_workspace_bytes(w.B, w.H, w.N, w.D, w.block), dtype=torch.uint8,
-                          device="cuda")
-        one_seg = [(bq, bk, dv, do)]
+        if not args.only_mask_select:
+            # one layer of a sparse step on the block-structured inputs: selection + attention as two calls
+            # (byte mask in between) and as the one call that writes the kept lists directly
+            tau3 = ra.rapid_mask_level_tau(3)
+            ws1 = torch.empty(ra.rapid_attn_joint_select_workspace_bytes(w.B, w.H, w.N, w.D, w.block), dtype=torch.uint8,
+                              device="cuda")
+            one_seg = [(bq, bk, dv, do)]
 
-        def two_calls():
-            ra.rapid_mask_select(bq, bk, sel_mask, w.block, w.kv_len, text_start, tau3, 0.0, sel_ws)
-            ra.rapid_attn_block_sparse(bq, bk, dv, do, sel_mask, w.block, w.kv_len, 0.0, ws)
+            def two_calls():
+                ra.rapid_mask_select(bq, bk, sel_mask, w.block, w.kv_len, text_start, tau3, 0.0, sel_ws)
+                ra.rapid_attn_block_sparse(bq, bk, dv, do, sel_mask, w.block, w.kv_len, 0.0, ws)
 
-        one_call = lambda: ra.rapid_attn_joint_select(one_seg, w.block, kv_len=w.kv_len, text_start=text_start,
-                                                      tau=tau3, workspace=ws1)
-        _, t2 = time_region(two_calls, 100, 10)
-        _, t1 = time_region(one_call, 100, 10)
-        out["mask_select"]["select_and_attend_level_3"] = {
-            "inputs": "block-structured", "kept_fraction": levels[2]["kept_fraction_block_structured_inputs"],
-            "two_calls_ms": round(t2, 5), "one_call_ms": round(t1, 5), "dense_ms": round(ev_mean, 5)}
-        del qk_sets, bq, bk, ws1
+            one_call = lambda: ra.rapid_attn_joint_select(one_seg, w.block, kv_len=w.kv_len, text_start=text_start,
+                                                          tau=tau3, workspace=ws1)
+            _, t2 = time_region(two_calls, 100, 10)
+            _, t1 = time_region(one_call, 100, 10)
+            out["mask_select"]["select_and_attend_level_3"] = {
+                "inputs": "block-structured", "kept_fraction": levels[2]["kept_fraction_block_structured_inputs"],
+                "two_calls_ms": round(t2, 5), "one_call_ms": round(t1, 5), "dense_ms": round(ev_mean, 5)}
+            del ws1
+        del qk_sets, bq, bk
 
     # ---- a scripted action trace of one image (counts as in the paper's appendix: 12-16 steps, 4-8 of
     # them reuse the cache, 2-4 run sparse attention) played against the library: the attention side
@@ -410,9 +422,12 @@ def main():
     # resolution (launch-latency bound) and one layer's hidden states (joint tokens x 3072 channels).
     if not args.no_cache_ops:
         cache = []
-        for label, elems in (("latent of one image: 4096 tokens x 64 channels", 4096 * 64),
-                             (f"hidden states of one layer: {w.N} tokens x 3072 channels", w.N * 3072),
-                             (f"hidden states of 8 layers: 8 x {w.N} tokens x 3072 channels", 8 * w.N * 3072)):
+        cases = (("latent of one image: 4096 tokens x 64 channels", 4096 * 64),
+                 (f"hidden states of one layer: {w.N} tokens x 3072 channels", w.N * 3072),
+                 (f"hidden states of 8 layers: 8 x {w.N} tokens x 3072 channels", 8 * w.N * 3072))
+        if args.only_cache_case is not None:
+            cases = cases[args.only_cache_case:args.only_cache_case + 1]
+        for label, elems in cases:
             # rotate over enough tensor sets to exceed the 256 MB memory-side cache, so that the
             # large case streams from HBM and not from that cache
             sets = max(1, min(8, int(600e6 // (6 * elems))))

@@ -23,11 +23,19 @@
 //   tiles          global -> LDS directly (global_load_lds_dwordx4), chunk-swizzled,
 //                  several tiles ahead of their use.
 // Kernels:
-//   attn_dense_pp_kernel   256 queries per workgroup, 8 wavefronts in two groups that
-//                          alternate a softmax phase and an MFMA phase in anti-phase
-//   attn_sparse_pp_kernel  one mask query-block per workgroup; the kept-tile list is
-//                          split between the two groups and merged at the end
-//   compact_mask_kernel, plan_kernel   kept-tile lists and launch order of the sparse path
+//   attn_dense_pp_kernel<D>     dense: 256 queries per workgroup, 8 wavefronts in two groups that
+//                               alternate a softmax phase and an MFMA phase in anti-phase
+//   attn_sparse_sg_kernel<D>    sparse, 128-token mask tiles: one four-wavefront workgroup per plan
+//                               record (a query-block or a piece of its kept list); pieces are
+//                               merged by the last one to finish
+//   attn_sparse_pp_kernel<D,2>  sparse, 64-token mask tiles: one query-block per workgroup, the kept
+//                               list split between two wavefront groups and merged through LDS
+//   plan_small_kernel           mask compaction and launch plan in one launch (up to 64 blocks per side)
+//   compact_mask_kernel, plan_split_kernel (128-token tiles), plan_kernel (64-token tiles)
+//                               the same in two launches for larger problems
+// Entry points (C ABI, bottom of the file): rapid_attn_dense, rapid_attn_block_sparse,
+// rapid_attn_block_sparse_static (scratch in a fixed array of this file), rapid_attn_joint,
+// rapid_attn_joint_select (selection kernels of rapid_mask.hip write the kept lists).
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
