@@ -328,7 +328,9 @@ def test_full_size_every_element(name, density):
     mask = w.mask(density)
     got, ws = run_sparse(q, k, v, mask, w.block, w.kv_len, return_ws=True)
     ref = oracle.attention(q, k, v, w.kv_len, mask, w.block)
-    assert_close(got, ref, f"{name} d={density} sparse entry")
+    e = assert_close(got, ref, f"{name} d={density} sparse entry")
+    print(f"{name} d={density} sparse entry, every element: max-abs {e['max_abs']:.3e} mean-abs {e['mean_abs']:.3e} "
+          f"rel-Frobenius {e['rel_fro']:.3e}")
     per_block_errors(got, ref, w.block, f"{name} d={density} sparse entry")
     assert (got[:, :, w.kv_len:] == 0).all()
     counts, order, index, g = read_plan(ws, w.B, w.H, w.nb, w.D, w.block)
@@ -339,7 +341,9 @@ def test_full_size_every_element(name, density):
         mask_is_full = density == 1.0
         got_d = run_dense(q, k, v, w.kv_len)
         ref_d = ref if mask_is_full else oracle.attention(q, k, v, w.kv_len)
-        assert_close(got_d, ref_d, f"{name} dense entry")
+        e = assert_close(got_d, ref_d, f"{name} dense entry")
+        print(f"{name} dense entry, every element: max-abs {e['max_abs']:.3e} mean-abs {e['mean_abs']:.3e} "
+              f"rel-Frobenius {e['rel_fro']:.3e}")
         per_block_errors(got_d, ref_d, w.block, f"{name} dense entry")
         assert (got_d[:, :, w.kv_len:] == 0).all()
 
@@ -390,7 +394,9 @@ def test_flux_2048_sparse_stratified(density):
                     np.int32)
     ref = oracle.attention_rows(q, k, v, rows, w.kv_len, mask, w.block)
     sel = got[rows[:, 0], rows[:, 1], rows[:, 2]]
-    assert_close(sel, ref, f"flux_2048 d={density}")
+    e = assert_close(sel, ref, f"flux_2048 d={density}")
+    print(f"flux_2048 d={density} sparse entry, {len(rows)} rows of {len(blocks)} (sample, head) pairs: max-abs {e['max_abs']:.3e} "
+          f"mean-abs {e['mean_abs']:.3e} rel-Frobenius {e['rel_fro']:.3e}")
     per_block_errors(sel.reshape(1, 1, -1, w.D), ref.reshape(1, 1, -1, w.D), w.block, f"flux_2048 d={density}")
     assert np.isfinite(widen(got)).all()
 
@@ -414,6 +420,8 @@ def test_flux_2048_dense_stratified():
     rows = np.array(rows, np.int32)
     ref = oracle.attention_rows(q, k, v, rows, w.kv_len)
     sel = got[rows[:, 0], rows[:, 1], rows[:, 2]]
-    assert_close(sel, ref, "flux_2048 dense")
+    e = assert_close(sel, ref, "flux_2048 dense")
+    print(f"flux_2048 dense entry, {len(rows)} rows: max-abs {e['max_abs']:.3e} mean-abs {e['mean_abs']:.3e} "
+          f"rel-Frobenius {e['rel_fro']:.3e}")
     per_block_errors(sel.reshape(1, 1, -1, w.D), ref.reshape(1, 1, -1, w.D), 256, "flux_2048 dense")
     assert np.isfinite(widen(got)).all()
