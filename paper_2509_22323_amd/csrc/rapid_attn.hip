@@ -777,7 +777,6 @@ __device__ __forceinline__ void item_mfma(const TileCtx<D, PD>& c, const bf16x8 
         acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, both), pb[g], acc[db], 0, 0, 0);
     } else {
         constexpr int t = (I - TI::NPV) / 2, rb = (I - TI::NPV) % 2;
-        // the first k-step starts from -m: the tile arrives as exponent differences
         f32x16 cin = st[rb];
         if constexpr (t == 0) {                            // first k-step starts from zero
 #pragma unroll
