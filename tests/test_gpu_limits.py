@@ -126,3 +126,42 @@ def test_selection_at_its_maximum_of_blocks_per_side():
     assert (lo <= got).all() and (got <= hi).all(), ((lo > got).sum(), (got > hi).sum())
     assert (got == mid).mean() >= 0.999
     assert got[0, 0, :nb - 4, :nb - 4].mean() < 0.95
+
+
+def test_more_items_per_xcd_than_the_planner_caches():
+    """4096 (sample, head) pairs of 9 query-blocks: 4608 items per XCD, more than the 4096 whose
+    lengths the planner keeps in LDS; the general planner (the one-launch planner stops at 1024
+    items per XCD).  Lists bit for bit, plan valid, sampled rows of a thousand items and of every
+    cut item against the oracle."""
+    B, H, N, D, block, kv_len = 2, 2048, 1152, 64, 128, 1100
+    nb = N // block
+    print(f"many items: B={B} H={H} N={N} items per XCD={B * H * nb // 8}", flush=True)
+    q, k, v = wl.make_qkv(B, H, N, D, kv_len, seed=4096, pad_fill="nan")
+    rng = np.random.Generator(np.random.PCG64(77))
+    mask = (rng.random((B, H, nb, nb)) < 0.4).astype(np.uint8)
+    mask[:, :, np.arange(nb), np.arange(nb)] = 1
+    mask[:, ::97, 3, :] = 1                             # some full rows
+    mask[1, 5::211, 2, :] = 0                           # some empty ones
+    dq, dk, dv = to_dev(q), to_dev(k), to_dev(v)
+    ws = torch.full((ra.rapid_attn_workspace_bytes(B, H, N, D, block),), 0xAB, dtype=torch.uint8, device="cuda")
+    o = torch.full_like(dq, float("nan"))
+    ra.rapid_attn_block_sparse(dq, dk, dv, o, torch.from_numpy(mask).cuda(), block, kv_len, 0.0, ws)
+    torch.cuda.synchronize()
+    got = from_dev(o)
+    counts, order, index, g = read_plan(ws.cpu().numpy(), B, H, nb, D, block)
+    want_counts, want_index = oracle.kept_tiles(mask, block, kv_len)
+    np.testing.assert_array_equal(counts, want_counts.reshape(-1))
+    want_index = want_index.reshape(-1, nb)
+    live = np.arange(nb)[None, :] < counts[:, None]
+    np.testing.assert_array_equal(np.where(live, index, -1), np.where(live, want_index, -1))
+    cut = check_plan(counts, order, g, B, H, nb, block, D)
+    print(f"  {len(cut)} of {B * H * nb} rows ran as pieces", flush=True)
+    items = sorted(set(int(x) for x in rng.integers(0, B * H * nb, 1000)) | set(cut))
+    rows = np.array([(it // nb // H, it // nb % H, (it % nb) * block + int(r)) for it in items
+                     for r in rng.integers(0, block, 2)], np.int32)
+    ref = oracle.attention_rows(q, k, v, rows, kv_len, mask, block)
+    e = assert_close(got[rows[:, 0], rows[:, 1], rows[:, 2]], ref, "many items")
+    print(f"  {len(rows)} rows of {len(items)} items: max-abs {e['max_abs']:.3e} mean-abs {e['mean_abs']:.3e}", flush=True)
+    full = widen(got)
+    assert np.isfinite(full).all() and (full[:, :, kv_len:] == 0).all()
+    assert (full[1, 5::211, 2 * block:3 * block] == 0).all()
