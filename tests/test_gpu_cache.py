@@ -90,3 +90,24 @@ def test_binding_rejects_wrong_tensors():
         ra.rapid_cache_reuse(a, a[:, :4].contiguous(), a)
     with pytest.raises(TypeError):
         ra.rapid_cache_reuse(a, a, a, torch.zeros(3, dtype=torch.uint8, device="cuda"))
+
+
+def test_more_than_two_to_the_32_elements():
+    """One sample of 2^32 + 24 elements (8.6 GB per tensor): element indices do not fit 32 bits.
+    The inputs repeat a seeded pattern whose length (2^20 + 7) does not divide 2^32, so an index
+    that wrapped would read another phase of it; the expected result is the oracle's for one
+    period, repeated the same way."""
+    period, n = (1 << 20) + 7, (1 << 32) + 24
+    o, x = tensors((1, period), seed=32, special=False)
+    reps = -(-n // period)
+
+    def tiled(bits):
+        return dev(bits).reshape(-1).repeat(reps)[:n].reshape(1, n)
+
+    d_o, d_x = tiled(o), tiled(x)
+    d_out = torch.empty((1, n), dtype=torch.bfloat16, device="cuda")
+    ra.rapid_cache_store(d_o, d_x, d_out)
+    want = co.cache_store(o, x)
+    assert torch.equal(d_out.view(torch.int16), tiled(want).view(torch.int16))
+    ra.rapid_cache_reuse(d_x, d_out, d_o)                     # d_o <- x + delta
+    assert torch.equal(d_o.view(torch.int16), tiled(co.cache_reuse(x, want)).view(torch.int16))
