@@ -53,8 +53,6 @@ namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
-typedef short s16x4 __attribute__((ext_vector_type(4)));
-typedef short s16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
@@ -1270,8 +1268,10 @@ __global__ __launch_bounds__(512, (D == 64 ? 4 : 2)) void attn_dense_pp_kernel(c
 // All LDS traffic of the main loop is explicit assembly, so stages are plain runtime
 // offsets into one array.
 // ---------------------------------------------------------------------------
+// (Waves per SIMD the register budget is set for: the 144 KB of stages at D = 128 leave room for
+// one workgroup per CU, 72 KB at D = 64 for two.)
 template <int D, int WPG>
-__global__ __launch_bounds__(128 * WPG, (D == 64 && WPG == 4 ? 4 : 2)) void attn_sparse_pp_kernel(const AttnParams p)
+__global__ __launch_bounds__(128 * WPG, (D == 64 ? (WPG == 4 ? 4 : 2) : 1)) void attn_sparse_pp_kernel(const AttnParams p)
 {
     typedef Geo<D> G;
     constexpr int PD = 6;
