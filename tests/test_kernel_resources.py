@@ -16,7 +16,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 @pytest.fixture(scope="module")
 def usage(tmp_path_factory):
     out = tmp_path_factory.mktemp("res") / "x.so"
-    cmd = [build.HIPCC] + build.FLAGS + ["-Rpass-analysis=kernel-resource-usage", "-o", str(out), build.SOURCES[0]]
+    cmd = [build.HIPCC] + build.FLAGS + ["-Rpass-analysis=kernel-resource-usage", "-o", str(out)] + build.SOURCES
     err = subprocess.run(cmd, capture_output=True, text=True, check=True).stderr
     kernels, cur = {"__stderr__": err}, None
     for line in err.splitlines():
@@ -44,6 +44,15 @@ def test_attention_kernels_stay_in_registers(usage, fragment, occupancy):
     u = usage[name[0]]
     assert u["ScratchSize [bytes/lane]"] == 0, u
     assert u["Occupancy [waves/SIMD]"] >= occupancy, u
+
+
+def test_no_kernel_of_the_library_uses_scratch_memory(usage):
+    """(Attention, planners, selection and Cache-Reuse kernels alike: a value that is spilled inside a
+    divergent region comes back stale for the lanes that sat the region out.)"""
+    kernels = {k: u for k, u in usage.items() if k != "__stderr__"}
+    assert len(kernels) >= 20, sorted(kernels)
+    bad = {k: u for k, u in kernels.items() if u.get("ScratchSize [bytes/lane]", 0) != 0}
+    assert not bad, bad
 
 
 def test_the_library_compiles_without_warnings(usage):
