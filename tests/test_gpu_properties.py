@@ -106,6 +106,39 @@ def test_runs_on_a_side_stream_without_sync_inside():
     assert_close(from_dev(o), oracle.attention(q, k, v), "side stream")
 
 
+def test_two_streams_with_their_own_workspaces():
+    """Sparse calls of two different problems issued alternately on two streams (default
+    priority), each with its own workspace: kernels of the two overlap on the chip, results are
+    bit-identical to the same calls made one after the other.  Both masks have rows long enough
+    to be cut into pieces, so partial results and piece counters of the two are live together."""
+    probs = []
+    for (H, N, D, seed) in [(24, 2304, 64, 231), (16, 2048, 128, 232)]:
+        q, k, v = wl.make_qkv(1, H, N, D, N - 40, seed=seed)
+        nb = N // 128
+        mask = wl.mask_bernoulli_diag(1, H, nb, 0.3, seed)
+        mask[:, :, nb - 2:, :] = 1                                   # two full rows per head
+        dq, dk, dv = to_dev(q), to_dev(k), to_dev(v)
+        dm = torch.from_numpy(mask).cuda()
+        ws = torch.empty(ra.rapid_attn_workspace_bytes(1, H, N, D, 128), dtype=torch.uint8, device="cuda")
+        o = torch.full_like(dq, float("nan"))
+        ra.rapid_attn_block_sparse(dq, dk, dv, o, dm, 128, N - 40, 0.0, ws)
+        torch.cuda.synchronize()
+        probs.append(dict(q=dq, k=dk, v=dv, m=dm, ws=ws, kv=N - 40, want=from_dev(o), o=torch.empty_like(dq),
+                          stream=torch.cuda.Stream()))
+        assert_close(probs[-1]["want"], oracle.attention(q, k, v, N - 40, mask, 128), "reference call")
+    for p in probs:
+        p["stream"].wait_stream(torch.cuda.current_stream())
+    for rep in range(12):
+        for p in probs:
+            with torch.cuda.stream(p["stream"]):
+                if rep == 11:
+                    p["o"].fill_(float("nan"))
+                ra.rapid_attn_block_sparse(p["q"], p["k"], p["v"], p["o"], p["m"], 128, p["kv"], 0.0, p["ws"])
+    for p in probs:
+        p["stream"].synchronize()
+        np.testing.assert_array_equal(from_dev(p["o"]), p["want"])
+
+
 def test_status_errors_raise_from_the_binding():
     q = torch.zeros(1, 1, 128, 64, dtype=torch.bfloat16, device="cuda")
     with pytest.raises(ra.RapidAttnError) as e:
