@@ -170,6 +170,9 @@ RAPID_API size_t rapid_attn_workspace_bytes(int B, int H, int N, int D, int bloc
  *                D <= stride_n <= 2^23; with two segments segments[0].n is a
  *                multiple of 128 (no 64-key tile and no 128-query block lies in
  *                both tensors) and stride_h, stride_n are the same in both.
+ *                The stride of a dimension of size 1 (stride_b when B == 1,
+ *                stride_h when H == 1, stride_n of a one-token second segment)
+ *                addresses nothing and is not looked at.
  */
 typedef struct rapid_attn_segment {
     const void* q;

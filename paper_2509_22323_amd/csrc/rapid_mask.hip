@@ -381,6 +381,9 @@ int joint_view(const rapid_attn_segment* segments, int n_segments, int B, int H,
     if (block != 64 && block != 128) return RAPID_ERR_UNSUPPORTED;
     if (text_start < 0 || !(tau > 0.f)) return RAPID_ERR_SHAPE;
     long long N = 0;
+    rapid_attn_segment seg[2];                    // strides of size-1 dimensions are not looked at
+    for (int i = 0; i < n_segments; ++i) seg[i] = rapid_internal::normalised_segment(segments[i], B, H, i == 1 ? &seg[0] : nullptr);
+    segments = seg;
     for (int i = 0; i < n_segments; ++i) {
         const rapid_attn_segment& g = segments[i];
         if (!g.q || !g.k) return RAPID_ERR_NULL;

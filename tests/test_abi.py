@@ -178,6 +178,13 @@ def test_joint_argument_errors_come_before_any_launch():
     assert joint([seg(n=200), seg(n=77)]) == S["RAPID_ERR_SHAPE"]            # first segment not a multiple of 128
     assert joint([seg(n=256), seg(n=77, in_stride_n=3 * 2 * 64)]) == S["RAPID_ERR_SHAPE"]   # token strides differ
     assert joint([seg(n=256), seg(n=77)], mask=A, ws=None) == S["RAPID_ERR_WORKSPACE"]
+    # strides of dimensions of size 1 address nothing and are not looked at: with B = 1, H = 1 and a
+    # one-token second segment, values that are refused elsewhere get as far as the workspace check
+    odd = dict(in_stride_b=3, out_stride_b=5, in_stride_h=7, out_stride_h=9)
+    assert joint([seg(n=256, H=1, **odd), seg(n=1, H=1, in_stride_n=17, out_stride_n=19, **odd)], H=1, mask=A,
+                 ws=None) == S["RAPID_ERR_WORKSPACE"]
+    assert joint([seg(n=256, **odd)], B=2, H=2, mask=A, ws=None) == S["RAPID_ERR_ALIGN"]
+    assert joint([seg(n=256), seg(n=2, in_stride_n=17)], mask=A, ws=None) == S["RAPID_ERR_ALIGN"]
     need = ra.rapid_attn_joint_workspace_bytes(1, 2, 333, 64, 128)
     assert need > 0 and need == ra.rapid_attn_joint_workspace_bytes(1, 2, 384, 64, 128)
     assert need == ra.rapid_attn_workspace_bytes(1, 2, 384, 64, 128)

@@ -58,6 +58,7 @@ CASES = [
     (2, 2, 256, 64, 128, 64, 0.5, True),
     (1, 3, 512, 33, 64, 64, 0.4, False),
     (2, 2, 333, 0, 128, 128, 0.5, True),       # one segment, ragged, token-major layout
+    (1, 2, 384, 1, 64, 128, 0.5, False),       # a one-token text segment: torch leaves its token stride at D
 ]
 
 
@@ -111,3 +112,33 @@ def test_joint_equals_the_contiguous_entry_points_bit_for_bit():
         ra.rapid_attn_joint([(dq, dk, dv, o2)], m, block, kv_len=500)
         torch.cuda.synchronize()
         assert torch.equal(o1.view(torch.int16), o2.view(torch.int16))
+
+
+def test_strides_of_size_one_dimensions_are_not_looked_at():
+    """B = 1, H = 1 and a one-token second segment, with strides in those dimensions that would be
+    refused (odd, unequal between the segments) if they addressed anything."""
+    B, H, n_img, n_txt, D, block = 1, 1, 256, 1, 128, 128
+    N = n_img + n_txt
+    q, k, v = wl.make_qkv(B, H, N, D, N, seed=91)
+    mask = wl.mask_bernoulli_diag(B, H, -(-N // block), 0.5, seed=9)
+    segs, _ = as_model_tensors(q, k, v, n_img, False)
+
+    def odd(t, sb, sh, sn):
+        return torch.as_strided(t, t.shape, (sb, sh, sn, 1), t.storage_offset())
+
+    (q0, k0, v0, o0), (q1, k1, v1, o1) = segs
+    segs = [(odd(q0, 3, 5, q0.stride(2)), odd(k0, 3, 5, k0.stride(2)), odd(v0, 3, 5, v0.stride(2)), odd(o0, 7, 9, o0.stride(2))),
+            (odd(q1, 11, 13, 17), odd(k1, 11, 13, 17), odd(v1, 11, 13, 17), odd(o1, 19, 21, 23))]
+    for m in (None, mask):
+        for (_, _, _, o) in segs:
+            o.fill_(float("nan"))
+        ra.rapid_attn_joint(segs, None if m is None else torch.from_numpy(m).cuda(), block)
+        torch.cuda.synchronize()
+        assert_close(gather(segs), oracle_joint(q, k, v, N, m, block), "size-one dimensions")
+    got = torch.full((B, H, 3, 3), 9, dtype=torch.uint8, device="cuda")
+    ra.rapid_mask_select_joint(segs, got, block, tau=0.9)
+    torch.cuda.synchronize()
+    want = torch.full_like(got, 9)
+    ra.rapid_mask_select_joint(as_model_tensors(q, k, v, n_img, False)[0], want, block, tau=0.9)
+    torch.cuda.synchronize()
+    assert torch.equal(got, want) and set(np.unique(got.cpu().numpy())) <= {0, 1}
