@@ -142,3 +142,35 @@ def test_strides_of_size_one_dimensions_are_not_looked_at():
     ra.rapid_mask_select_joint(as_model_tensors(q, k, v, n_img, False)[0], want, block, tau=0.9)
     torch.cuda.synchronize()
     assert torch.equal(got, want) and set(np.unique(got.cpu().numpy())) <= {0, 1}
+
+
+def test_per_sample_lengths_outside_the_range_are_clamped():
+    """kv_lens below 0 count as 0 (the sample outputs zeros), above N as N: attention (dense and
+    sparse), selection and the one-call form give what the clamped lengths give, bit for bit."""
+    B, H, n_img, n_txt, D, block = 3, 2, 256, 77, 64, 128
+    N = n_img + n_txt
+    nb = -(-N // block)
+    q, k, v = wl.make_qkv(B, H, N, D, N, seed=55)
+    mask = torch.from_numpy(wl.mask_bernoulli_diag(B, H, nb, 0.5, seed=2)).cuda()
+    wild = torch.tensor([-7, N + 1000, 200], dtype=torch.int32, device="cuda")
+    tame = torch.tensor([0, N, 200], dtype=torch.int32, device="cuda")
+    outs = {}
+    for name, lens in (("wild", wild), ("tame", tame)):
+        res = []
+        for m in (None, mask):
+            segs, _ = as_model_tensors(q, k, v, n_img, True)
+            ra.rapid_attn_joint(segs, m, block, kv_lens=lens)
+            torch.cuda.synchronize()
+            res.append(gather(segs))
+        segs, _ = as_model_tensors(q, k, v, n_img, True)
+        sel = torch.full((B, H, nb, nb), 9, dtype=torch.uint8, device="cuda")
+        ra.rapid_mask_select_joint(segs, sel, block, kv_lens=lens, text_start=n_img, tau=0.8)
+        sel2 = torch.full_like(sel, 9)
+        ra.rapid_attn_joint_select(segs, block, kv_lens=lens, text_start=n_img, tau=0.8, mask_out=sel2)
+        torch.cuda.synchronize()
+        res += [sel.cpu().numpy(), sel2.cpu().numpy(), gather(segs)]
+        outs[name] = res
+    for a, b in zip(outs["wild"], outs["tame"]):
+        np.testing.assert_array_equal(a, b)
+    assert (outs["wild"][0][0] == 0).all() and (outs["wild"][3][0] == 0).all()
+    assert_close(outs["wild"][0][1:2], oracle_joint(q[1:2], k[1:2], v[1:2], N, None, block), "length above N")
