@@ -29,7 +29,7 @@ def test_bench_prints_one_json_line_with_roofline_and_cpu_baseline():
     r = d["roofline"]
     assert r["bound"] == "mfma" and r["unit"] == "TFLOP/s" and r["peak"] == 2500.0
     assert abs(r["frac"] - r["achieved"] / r["peak"]) < 1e-3 and 0.2 < r["frac"] < 1.0
-    assert abs(d["value"] - r["achieved"]) / d["value"] < 0.05          # same region, two clocks
+    assert abs(d["value"] - r["achieved"]) / d["value"] < 0.15          # same region, two clocks
     assert r["traffic"] is None or r["traffic"] >= r["algorithmic_bytes"] * 0.9
     c = d["cpu_baseline"]
     assert c["kind"] == "oracle" and c["cores"] >= 1 and c["value"] > 0 and isinstance(c["sample"], str)
